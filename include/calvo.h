@@ -1,0 +1,143 @@
+/*
+ * calvo.h - C ABI of the MI355X prefix-hit prefill path.
+ *
+ * The path is the part of the CALVO serving design that runs on one GPU and its
+ * host: reusable KVCache blocks that already sit in local host DRAM (the
+ * paper's L2 tier, Section 2.2) are loaded into a paged KV space in HBM (L1)
+ * and the prefill of the not-yet-computed query tokens runs over them
+ * (Section 3.1: each loading stage moves a block once its source is ready and
+ * its destination is allocated, signals completion upward, and compute starts
+ * as soon as the blocks it needs are resident).  Here residency is tracked per
+ * transformer layer, so attention of layer l overlaps loading of layers l+1...
+ *
+ * Conventions
+ *  - Every function returns a status (CALVO_OK == 0, errors negative) and never
+ *    aborts or throws.  calvo_last_error() gives a thread-local message.
+ *  - All argument validation happens on the host before any device work is
+ *    queued: a call that fails with CALVO_EINVAL / CALVO_ENOMEM has written
+ *    nothing.
+ *  - "DEVICE" pointers are HIP device memory of the current device, "HOST"
+ *    pointers ordinary host memory, "PINNED" page-locked host memory obtained
+ *    from hipHostMalloc (or a framework's pinned allocator).  The library never
+ *    frees, reallocates or keeps caller memory beyond what each call states.
+ *  - Element type: CALVO_BF16 (2 bytes, upper half of an IEEE fp32) or
+ *    CALVO_F32.  The ingest path moves bytes and does not interpret them.
+ *
+ * Layouts (B = block_tokens, Hkv = n_kv_heads, D = head_dim; C order)
+ *    pool      [n_layers][pool_blocks][2][B][Hkv][D]   2 = K then V
+ *    host KV   [n_layers][host blocks][2][B][Hkv][D]   one layer every host_layer_stride bytes
+ *    q, out    [total suffix tokens][Hq][D]            requests concatenated, see cu_suffix
+ *    k_suffix, v_suffix  [total suffix tokens][Hkv][D]
+ * The paper names blocks, tiers and the context/query split but no block size,
+ * layout or precision; these are this library's definitions.
+ */
+#ifndef CALVO_H
+#define CALVO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct calvo_ctx calvo_ctx; /* opaque: streams, staging buffers, per-layer events, table cache */
+
+enum { CALVO_OK = 0, CALVO_EINVAL = -1, CALVO_ENOMEM = -2, CALVO_EHIP = -3, CALVO_ENOTREADY = -4 };
+enum { CALVO_BF16 = 0, CALVO_F32 = 1 };
+enum { CALVO_EV_QUERY = 0, CALVO_EV_HOST_WAIT = 1, CALVO_EV_STREAM_WAIT = 2 };
+
+typedef struct {
+  int32_t n_layers;
+  int32_t n_q_heads;     /* multiple of n_kv_heads */
+  int32_t n_kv_heads;
+  int32_t head_dim;      /* multiple of 8, at most 256; the bf16 MFMA kernel needs 128 */
+  int32_t block_tokens;  /* B; must be 16 */
+  int32_t dtype;         /* CALVO_BF16 or CALVO_F32 */
+  int64_t pool_blocks;   /* slots per layer */
+  void*   pool;          /* DEVICE, caller-owned, 16-byte aligned; must outlive the context */
+  size_t  staging_bytes; /* size of each device staging buffer (a whole number of blocks is used);
+                            0 selects the zero-copy ingest: the scatter kernel reads the pinned
+                            host blocks directly over PCIe and no staging buffer is allocated */
+  int32_t n_staging;     /* number of staging buffers in the ring, 2..8 (0 = 2) */
+  int32_t n_copy_streams;/* 1 or 2 streams issuing the host-to-device copies (0 = 1) */
+  void*   compute_stream;/* hipStream_t the attention work is queued on, caller-owned;
+                            NULL = the library creates and owns one */
+} calvo_config;
+
+/* One request: a reusable context of n_prefix_blocks whole blocks (already held in
+ * host DRAM) followed by suffix_len tokens that are computed now (paper, Section
+ * 2.2: static application context + dynamic user query). */
+typedef struct {
+  const void*    host_kv;            /* PINNED, caller-owned: block j of layer l starts at
+                                        host_kv + l*host_layer_stride + j*block_bytes.  Must stay valid
+                                        and unchanged until the last requested layer's event has fired. */
+  int64_t        host_layer_stride;  /* bytes between consecutive layers */
+  const int32_t* block_table;        /* HOST: n_prefix_blocks + ceil(suffix_len/B) slot ids in
+                                        [0, pool_blocks), pairwise distinct; read during the call only */
+  int32_t        n_prefix_blocks;    /* P / B */
+  int32_t        first_ingest_block; /* blocks [0, first) are already resident in the pool (a prefix run
+                                        shared with an earlier request) and are not loaded; usually 0 */
+  int32_t        suffix_len;         /* S >= 0 */
+} calvo_request;
+
+/* Create a context for one pool.  Allocates the staging ring, one event per layer and
+ * the internal streams on the current device.  CALVO_EINVAL for a bad shape or NULL pool,
+ * CALVO_ENOMEM / CALVO_EHIP if a device resource cannot be obtained (nothing is leaked). */
+int calvo_create(const calvo_config* cfg, calvo_ctx** out);
+
+/* Waits for all work queued through the context, then releases what calvo_create made.
+ * The pool and the caller's stream are left alone. */
+int calvo_destroy(calvo_ctx* ctx);
+
+/* L2 -> L1 loading stage (paper Section 3.1; footnote of Section 4.1: several concurrent
+ * loads are needed to fill PCIe).  For every request r, layer l in [layer_begin, layer_end)
+ * and prefix block j in [first_ingest_block, n_prefix_blocks):
+ *     pool[l][block_table[j]]  <-  host block j of layer l        (raw bytes, bit exact)
+ * No other pool byte is written.  Asynchronous: the call queues copy-engine transfers into
+ * the staging ring and scatter kernels on internal streams, records layer l's event after
+ * the last store of layer l, and returns.  Layers are issued in ascending order.
+ * Errors (nothing queued): CALVO_EINVAL for NULL pointers, a layer range outside
+ * [0, n_layers], slot ids outside the pool or repeated inside one request, negative counts,
+ * first_ingest_block > n_prefix_blocks, a host_layer_stride smaller than the request's
+ * blocks; CALVO_EHIP if HIP refuses a transfer (queued work so far still completes). */
+int calvo_kv_ingest(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end);
+
+/* Per-layer "blocks are resident" signal (paper Section 3.1: a stage signals the stage above
+ * when a block has been loaded).  mode:
+ *   CALVO_EV_QUERY        CALVO_OK if layer's ingest has finished, else CALVO_ENOTREADY
+ *   CALVO_EV_HOST_WAIT    block the calling thread until it has
+ *   CALVO_EV_STREAM_WAIT  make `stream` (a hipStream_t; NULL = the compute stream) wait for
+ *                         it on the device; the host does not block
+ * A layer that was never ingested through this context counts as ready. */
+int calvo_layer_event(calvo_ctx* ctx, int layer, int mode, void* stream);
+
+/* Compute stage for one layer (paper Section 2.1 prefill over a reused prefix; Section 3.1:
+ * launched once the needed blocks are resident).  Queued on the compute stream, after a
+ * device-side wait on layer's ingest event:
+ *   1. if k_suffix/v_suffix are non-NULL, the suffix tokens' K and V are written to the
+ *      request's suffix slots (token i of request r at absolute position P_r + i);
+ *   2. out[i][h][:] = sum_t softmax_t(scale * <q[i][h], K[t][g]>) V[t][g],  t = 0 .. P_r + i,
+ *      g = h / (Hq/Hkv), K/V fetched through the block table.
+ * q, k_suffix, v_suffix, out: DEVICE, 16-byte aligned, layouts above, element type = dtype
+ * (accumulation is fp32; bf16 output is rounded to nearest even).  cu_suffix: HOST,
+ * n_reqs+1 ascending offsets into the token dimension, cu_suffix[0] == 0 and
+ * cu_suffix[r+1]-cu_suffix[r] == reqs[r].suffix_len.  scale <= 0 selects 1/sqrt(D).
+ * Block tables are copied during the call.  Tokens stored after position P+S-1 in the last
+ * slot are never read.  Returns CALVO_EINVAL (nothing queued) on NULL / misaligned pointers,
+ * inconsistent cu_suffix, bad layer or bad slot ids. */
+int calvo_prefill_attn(calvo_ctx* ctx, int layer, const void* q, const void* k_suffix, const void* v_suffix,
+                       void* out, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale);
+
+/* Measurement helper: duration in milliseconds of the most recent attention kernel queued by
+ * calvo_prefill_attn for `layer` (HIP events recorded around the kernel on the compute
+ * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */
+int calvo_attn_kernel_ms(calvo_ctx* ctx, int layer, float* ms);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* calvo_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CALVO_H */

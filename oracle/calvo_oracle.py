@@ -173,6 +173,43 @@ def prefill_attn(pool_layer: np.ndarray, q: np.ndarray, table, prefix_len: int, 
     return out
 
 
+def attn_rows(q_rows: np.ndarray, K: np.ndarray, V: np.ndarray, n_visible, scale: float) -> np.ndarray:
+    """The same definition for several query rows of one head at once, in matrix form:
+    scores = scale * Q K^T, keys at index >= n_visible[r] are excluded from row r, softmax
+    along keys, times V.  q_rows is [R][D] fp64, n_visible[r] = P + i_r + 1.  No running
+    maximum, no tiling: every row's full score vector is formed."""
+    n_visible = np.asarray(n_visible, dtype=np.int64)
+    n_max = int(n_visible.max())
+    s = scale * (q_rows @ K[:n_max].T)                        # [R][n_max]
+    hidden = np.arange(n_max)[None, :] >= n_visible[:, None]
+    s[hidden] = -np.inf
+    w = np.exp(s - s.max(axis=1, keepdims=True))
+    return (w @ V[:n_max]) / w.sum(axis=1, keepdims=True)
+
+
+def prefill_attn_sampled(pool_layer: np.ndarray, q: np.ndarray, table, prefix_len: int, suffix_len: int,
+                         block_tokens: int, rows, scale=None) -> np.ndarray:
+    """prefill_attn restricted to the suffix rows in `rows`, all heads, using attn_rows
+    (one matrix product per head).  Meant for long contexts where only a sample of the
+    output rows is checked.  Returns [len(rows)][Hq][D]."""
+    S, Hq, D = q.shape
+    assert S == suffix_len
+    Hkv = pool_layer.shape[3]
+    G = Hq // Hkv
+    if scale is None:
+        scale = np.float32(1.0) / np.sqrt(np.float32(D))
+    scale = float(np.float32(scale))
+    rows = np.asarray([int(r) for r in rows], dtype=np.int64)
+    out = np.zeros((len(rows), Hq, D), np.float64)
+    n_vis = prefix_len + rows + 1
+    qf = widen(q[rows])
+    for g in range(Hkv):
+        K, V = gather_kv_blocks(pool_layer, table, int(n_vis.max()), g, block_tokens)
+        for h in range(g * G, (g + 1) * G):
+            out[:, h] = attn_rows(qf[:, h], K, V, n_vis, scale)
+    return out
+
+
 def prefill_attn_batch(pool_layer, q, requests, cu_suffix, block_tokens, scale=None):
     """All requests of a batch; q is [sum S][Hq][D], requests is a list of
     (table, prefix_len, suffix_len).  Returns [sum S][Hq][D] fp64."""

@@ -1,0 +1,145 @@
+"""ctypes binding of libcalvo.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path (scatter, suffix append, attention, events) runs inside
+the library's HIP code; nothing here computes.  PyTorch is used by callers for
+device memory, pinned memory and streams; this module accepts raw addresses
+(ints) or objects with a data_ptr() method.
+
+The library must have been built (python -m paper_2603_21257_amd.build, or
+__graft_entry__.build()); loading fails loudly otherwise - there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+CALVO_OK, CALVO_EINVAL, CALVO_ENOMEM, CALVO_EHIP, CALVO_ENOTREADY = 0, -1, -2, -3, -4
+CALVO_BF16, CALVO_F32 = 0, 1
+CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
+EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_layer_event", "calvo_prefill_attn",
+           "calvo_attn_kernel_ms", "calvo_last_error"]
+
+
+class calvo_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("dtype", C.c_int32),
+                ("pool_blocks", C.c_int64), ("pool", C.c_void_p), ("staging_bytes", C.c_size_t),
+                ("n_staging", C.c_int32), ("n_copy_streams", C.c_int32), ("compute_stream", C.c_void_p)]
+
+
+class calvo_request(C.Structure):
+    _fields_ = [("host_kv", C.c_void_p), ("host_layer_stride", C.c_int64), ("block_table", C.POINTER(C.c_int32)),
+                ("n_prefix_blocks", C.c_int32), ("first_ingest_block", C.c_int32), ("suffix_len", C.c_int32)]
+
+
+class CalvoError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"calvo error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_21257_amd.build` "
+                               "(there is no CPU fallback for the HIP path)")
+        L = C.CDLL(LIB_PATH)
+        L.calvo_create.argtypes = [C.POINTER(calvo_config), C.POINTER(C.c_void_p)]
+        L.calvo_destroy.argtypes = [C.c_void_p]
+        L.calvo_kv_ingest.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int]
+        L.calvo_layer_event.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
+        L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
+        L.calvo_last_error.argtypes = []
+        L.calvo_last_error.restype = C.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def calvo_last_error() -> str:
+    return lib().calvo_last_error().decode()
+
+
+def _check(rc: int, ok=(CALVO_OK,)) -> int:
+    if rc not in ok:
+        raise CalvoError(rc, calvo_last_error())
+    return rc
+
+
+def make_request(host_kv, host_layer_stride: int, block_table: np.ndarray, n_prefix_blocks: int,
+                 suffix_len: int, first_ingest_block: int = 0) -> calvo_request:
+    """Marshal one request.  The returned struct keeps the table array alive."""
+    tab = np.ascontiguousarray(block_table, dtype=np.int32)
+    r = calvo_request(_ptr(host_kv), int(host_layer_stride), tab.ctypes.data_as(C.POINTER(C.c_int32)),
+                      int(n_prefix_blocks), int(first_ingest_block), int(suffix_len))
+    r._keep = tab
+    return r
+
+
+def _req_array(reqs: Sequence[calvo_request]):
+    arr = (calvo_request * max(len(reqs), 1))()
+    for i, r in enumerate(reqs):
+        arr[i] = r
+    arr._keep = list(reqs)
+    return arr
+
+
+def calvo_create(n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, pool_blocks: int,
+                 pool, staging_bytes: int = 0, n_staging: int = 0, n_copy_streams: int = 0,
+                 compute_stream=None, block_tokens: int = 16) -> int:
+    """Returns the context handle (an address)."""
+    cfg = calvo_config(n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, dtype, pool_blocks, _ptr(pool),
+                       staging_bytes, n_staging, n_copy_streams,
+                       None if compute_stream is None else int(compute_stream))
+    out = C.c_void_p()
+    _check(lib().calvo_create(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def calvo_destroy(ctx: int) -> None:
+    _check(lib().calvo_destroy(ctx))
+
+
+def calvo_kv_ingest(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int) -> None:
+    _check(lib().calvo_kv_ingest(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end))
+
+
+def calvo_layer_event(ctx: int, layer: int, mode: int, stream=None) -> bool:
+    """True when the layer is ready (always, for the two waiting modes)."""
+    rc = lib().calvo_layer_event(ctx, layer, mode, None if stream is None else int(stream))
+    return _check(rc, ok=(CALVO_OK, CALVO_ENOTREADY)) == CALVO_OK
+
+
+def calvo_prefill_attn(ctx: int, layer: int, q, k_suffix, v_suffix, out, reqs: Sequence[calvo_request],
+                       cu_suffix: np.ndarray, scale: float = 0.0) -> None:
+    cu = np.ascontiguousarray(cu_suffix, dtype=np.int32)
+    _check(lib().calvo_prefill_attn(ctx, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out),
+                                    _req_array(reqs), len(reqs), cu.ctypes.data_as(C.POINTER(C.c_int32)),
+                                    float(scale)))
+
+
+def calvo_attn_kernel_ms(ctx: int, layer: int) -> float:
+    ms = C.c_float()
+    _check(lib().calvo_attn_kernel_ms(ctx, layer, C.byref(ms)))
+    return ms.value

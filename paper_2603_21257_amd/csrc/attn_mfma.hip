@@ -1,0 +1,304 @@
+// Paged causal GQA prefill attention for gfx950 (CDNA4): bf16 storage, head_dim 128,
+// bf16 MFMA (v_mfma_f32_32x32x16_bf16) for both contractions, fp32 online softmax.
+//
+// Work decomposition
+//   workgroup = 4 wavefronts = one tile of suffix tokens x up to 4 query heads that share
+//   one KV head; the K/V tile it streams is staged once in LDS and used by all 4 waves.
+//   Each wave owns NT*32 query rows (one head) and keeps their Q, O and softmax state in
+//   registers for the whole key loop.
+//
+// Transposed formulation (so that every softmax statistic is lane-local):
+//   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile (LDS, d-contiguous), B = Q (registers)
+//   O^T[d][query]  += V^T[d][key] * P^T[key][query] A = V^T, B = P^T
+//   In the 32x32 accumulator layout a lane holds one query column and 16 keys, so row max /
+//   row sum are reductions inside a lane plus one exchange with lane^32, the O rescale is a
+//   per-lane scalar, and P^T is already the B operand of the second MFMA: the MFMA k index is
+//   only a summation index, so the 8 keys a lane holds after QK^T (key = 8*(r/4)+4*(lane/32)+r%4)
+//   are used as they are, and the V^T operand is fetched for exactly those keys.
+//   V sits in LDS token-major (as in the pool); the d-major operand is produced by the
+//   LDS transpose read ds_read_b64_tr_b16: inside a 16-lane group, lane i receives element
+//   i%4 of the four 8-byte rows addressed by lanes i/4, i/4+4, i/4+8, i/4+12.
+//
+// LDS: two buffers of (K 64x128 + V 64x128) bf16, 16-byte chunks XOR-swizzled so that the
+// operand reads (K: 16 consecutive rows, same chunk; V: 4 rows x 64 bytes) hit distinct banks.
+#include "calvo_internal.h"
+
+namespace calvo {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+constexpr int kD = 128;          // head_dim
+constexpr int kKT = 64;          // keys per LDS tile
+constexpr int kRowB = kD * 2;    // bytes per token row of one head
+constexpr int kTileB = kKT * kRowB;          // 16 KiB
+constexpr int kLdsBytes = 2 * 2 * kTileB;    // double-buffered K and V
+
+__device__ inline int k_swz(int row, int chunk) { return row * kRowB + ((chunk ^ (row & 15)) << 4); }
+__device__ inline int v_swz(int row, int chunk) { return row * kRowB + ((chunk ^ ((row & 3) << 2)) << 4); }
+
+template <int NT>
+__global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31;       // query column inside a 32-wide tile
+  const int lh = lane >> 5;       // which half of the k index this lane feeds
+
+  // ---- which tile of which request, which head group (wave-uniform)
+  const int HW = p.heads_per_wg;
+  const int TPW = 4 / HW;                         // token sub-tiles per workgroup
+  const int NHG = p.n_q_heads / HW;
+  int it, hg;
+  {
+    const int bid = blockIdx.x;
+    if ((NHG & 7) == 0) {                         // keep one KV head's workgroups on one XCD
+      const int per = NHG >> 3, rest = bid >> 3;
+      hg = (bid & 7) * per + rest % per;
+      it = rest / per;
+    } else {
+      hg = bid % NHG;
+      it = bid / NHG;
+    }
+  }
+  const WorkItem wi = p.items[it];
+  const ReqDesc rd = p.reqs[wi.req];
+  const int P = rd.prefix_len, S = rd.suffix_len;
+  const int TQ = 32 * NT * TPW;
+  const int q_base = wi.q_tile * TQ;
+  const int hq = hg * HW + wave % HW;
+  const int kv = hq / (p.n_q_heads / p.n_kv_heads);
+  const int wq0 = q_base + (wave / HW) * 32 * NT;            // first suffix token of this wave
+  const bool wave_active = wq0 < S;
+  const int pq_min = P + wq0;
+  const int pq_max = P + min(wq0 + 32 * NT, S) - 1;
+  const int ctx_len = P + S;
+  const int n_keys = P + min(q_base + TQ, S);
+  const int n_tiles = (n_keys + kKT - 1) / kKT;
+  const int last_blk = (ctx_len + kBlockTokens - 1) / kBlockTokens - 1;
+  const int32_t* table = p.tables + rd.table_off;
+  const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
+  const float c2 = p.scale * 1.4426950408889634f;            // scores are exponentiated in base 2
+
+  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8]
+  bf16x8 qB[NT][8];
+  {
+    const unsigned short* q = (const unsigned short*)p.q;
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+      const int tokq = wq0 + nt * 32 + ln;
+      const bool ok = tokq < S;
+      const unsigned short* row = q + ((int64_t)(rd.q_off + (ok ? tokq : 0)) * Hq + hq) * kD + 8 * lh;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (ok) v = *(const u32x4*)(row + 16 * ks);
+        qB[nt][ks] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+  }
+
+  f32x16 o[4][NT];
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) o[dt][nt][r] = 0.f;
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; nt++) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
+
+  // ---- global -> register -> LDS staging of one 64-key tile (4 K chunks + 4 V chunks per lane)
+  const unsigned char* pool = (const unsigned char*)p.pool_layer;
+  const int64_t half_b = (int64_t)kBlockTokens * Hkv * kD * 2;        // bytes of the K half of a block
+  const int ld_row = tid >> 4;      // 0..15: token row inside a block; block i of the tile = i
+  const int ld_chunk = tid & 15;
+  const int64_t ld_off = (int64_t)ld_row * Hkv * kD * 2 + (int64_t)kv * kD * 2 + ld_chunk * 16;
+  u32x4 kreg[4], vreg[4];
+
+  auto load_tile = [&](int tile) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int blk = min(tile * 4 + i, last_blk);
+      const int64_t slot = __builtin_amdgcn_readfirstlane(table[blk]);
+      const unsigned char* src = pool + slot * 2 * half_b + ld_off;
+      const int t = tile * kKT + i * 16 + ld_row;
+      kreg[i] = *(const u32x4*)src;
+      u32x4 v = *(const u32x4*)(src + half_b);
+      if (t >= ctx_len) v = (u32x4){0u, 0u, 0u, 0u};   // undefined tokens must not reach the PV product
+      vreg[i] = v;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    unsigned char* kb = smem + buf * 2 * kTileB;
+    unsigned char* vb = kb + kTileB;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int row = i * 16 + ld_row;
+      *(u32x4*)(kb + k_swz(row, ld_chunk)) = kreg[i];
+      *(u32x4*)(vb + v_swz(row, ld_chunk)) = vreg[i];
+    }
+  };
+
+  // lane-constant parts of the operand addresses
+  const int g16 = lane >> 4, s16 = lane & 15;
+  // V^T operand: 16-lane group g16 covers d = 16*(g16&1) .. +16 of the 32-wide d tile and the
+  // 4 tokens starting at 4*(g16>>1); source lane s16 points at token s16/4, d offset 4*(s16%4).
+  const int v_row0 = 4 * (g16 >> 1) + (s16 >> 2);
+  const int v_chunk0 = 2 * (g16 & 1) + ((s16 & 3) >> 1);
+  const int v_byte = (s16 & 1) * 8;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; tile++) {
+    const int buf = tile & 1;
+    if (tile + 1 < n_tiles) load_tile(tile + 1);
+    const unsigned char* kb = smem + buf * 2 * kTileB;
+    const unsigned char* vb = kb + kTileB;
+
+#pragma unroll
+    for (int sb = 0; sb < 2; sb++) {
+      const int k0 = tile * kKT + sb * 32;
+      if (wave_active && k0 <= pq_max) {
+        // ---- S^T = K Q^T
+        f32x16 s[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; nt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) s[nt][r] = 0.f;
+        const int krow = sb * 32 + ln;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+          const bf16x8 a = *(const bf16x8*)(kb + k_swz(krow, 2 * ks + lh));
+#pragma unroll
+          for (int nt = 0; nt < NT; nt++)
+            s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qB[nt][ks], s[nt], 0, 0, 0);
+        }
+        // ---- causal mask (only near the diagonal)
+        if (k0 + 31 > pq_min) {
+#pragma unroll
+          for (int nt = 0; nt < NT; nt++) {
+            const int pq = pq_min + nt * 32 + ln;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+              const int kt = k0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+              if (kt > pq) s[nt][r] = -INFINITY;
+            }
+          }
+        }
+        // ---- online softmax, lane-local per query column
+        bf16x8 pb[NT][2];
+        float alpha[NT];
+        bool changed = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; nt++) {
+          float mx = s[nt][0];
+#pragma unroll
+          for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[nt][r]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run[nt], mx);
+          alpha[nt] = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * c2);
+          changed |= (m_new != m_run[nt]);
+          m_run[nt] = m_new;
+          const float mc = m_new * c2;
+          float ps = 0.f;
+          float pv[16];
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][r], c2, -mc));
+            ps += pv[r];
+          }
+          l_run[nt] = l_run[nt] * alpha[nt] + ps;
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) pb[nt][j][e] = (__bf16)pv[8 * j + e];
+        }
+        if (__builtin_amdgcn_ballot_w64(changed) != 0) {
+#pragma unroll
+          for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+            for (int nt = 0; nt < NT; nt++)
+#pragma unroll
+              for (int r = 0; r < 16; r++) o[dt][nt][r] *= alpha[nt];
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+#pragma unroll
+          for (int dt = 0; dt < 4; dt++) {
+            const int row_a = sb * 32 + 16 * j + v_row0;
+            const int chunk = 4 * dt + v_chunk0;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3)))*)(vb + v_swz(row_a, chunk) + v_byte));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3)))*)(vb + v_swz(row_a + 8, chunk) + v_byte));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+            for (int nt = 0; nt < NT; nt++)
+              o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[nt][j], o[dt][nt], 0, 0, 0);
+          }
+        }
+      }
+    }
+
+    if (tile + 1 < n_tiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- normalise and write O[token][head][d]; lane holds d = 32dt + 8(r/4) + 4lh + r%4
+  if (wave_active) {
+    unsigned short* out = (unsigned short*)p.out;
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+      const float lt = l_run[nt] + __shfl_xor(l_run[nt], 32);
+      const float inv = 1.f / lt;
+      const int tokq = wq0 + nt * 32 + ln;
+      if (tokq < S) {
+        unsigned short* row = out + ((int64_t)(rd.q_off + tokq) * Hq + hq) * kD + 4 * lh;
+#pragma unroll
+        for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+          for (int rq = 0; rq < 4; rq++) {
+            bf16x2 a, b;
+            a[0] = (__bf16)(o[dt][nt][4 * rq + 0] * inv);
+            a[1] = (__bf16)(o[dt][nt][4 * rq + 1] * inv);
+            b[0] = (__bf16)(o[dt][nt][4 * rq + 2] * inv);
+            b[1] = (__bf16)(o[dt][nt][4 * rq + 3] * inv);
+            u32x2 w = {__builtin_bit_cast(unsigned int, a), __builtin_bit_cast(unsigned int, b)};
+            *(u32x2*)(row + 32 * dt + 8 * rq) = w;
+          }
+      }
+    }
+  }
+}
+
+constexpr int kNT = 2;
+
+int attn_mfma_tile_tokens(int heads_per_wg) { return 32 * kNT * (4 / heads_per_wg); }
+
+hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
+  if (p.n_items <= 0) return hipSuccess;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<kNT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const unsigned grid = (unsigned)p.n_items * (unsigned)(p.n_q_heads / p.heads_per_wg);
+  hipLaunchKernelGGL(attn_mfma_kernel<kNT>, dim3(grid), dim3(256), kLdsBytes, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace calvo

@@ -1,0 +1,490 @@
+// Host side of libcalvo: argument validation, the ingest pipeline (paper Section 3.1,
+// the L2->L1 loading stage with its per-layer completion signal), the block-table cache
+// and the launch of the compute stage.  See include/calvo.h for the contract.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/calvo.h"
+#include "calvo_internal.h"
+
+using namespace calvo;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+  (void)hipGetLastError();  // clear the sticky per-thread error
+  return fail(e == hipErrorOutOfMemory ? CALVO_ENOMEM : CALVO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr)                                  \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) return fail_hip(e_, #expr);  \
+  } while (0)
+
+}  // namespace
+
+struct calvo_ctx {
+  calvo_config cfg{};
+  size_t elt = 0, blk_bytes = 0;
+  int64_t layer_bytes = 0;
+  int n_staging = 0, n_copy = 0;
+  int64_t staging_blocks = 0;
+  hipStream_t s_copy[2] = {nullptr, nullptr};
+  hipStream_t s_scatter = nullptr;
+  hipStream_t s_compute = nullptr;
+  bool own_compute = false;
+  std::vector<void*> staging;
+  std::vector<hipEvent_t> ev_filled, ev_free;
+  std::vector<char> free_recorded;
+  uint64_t seq = 0;
+  std::vector<hipEvent_t> ev_layer;
+  std::vector<char> layer_issued;
+  // ingest-side table copy (device) and its pinned shadow
+  int32_t* d_tab_ing = nullptr;
+  int32_t* h_tab_ing = nullptr;
+  size_t tab_ing_cap = 0;
+  hipEvent_t ev_tab_ing = nullptr;
+  bool tab_ing_pending = false;
+  // attention-side descriptor blob: [ReqDesc x n][WorkItem x m][tables]
+  int32_t* d_att = nullptr;
+  int32_t* h_att = nullptr;
+  size_t att_cap = 0;     // in int32
+  size_t att_len = 0;     // valid int32 in the shadow == on device
+  hipEvent_t ev_att = nullptr;
+  bool att_pending = false;
+  std::vector<hipEvent_t> ev_t0, ev_t1;
+  std::vector<char> timed;
+  int scatter_grid = 64;
+};
+
+namespace {
+
+void destroy_partial(calvo_ctx* c) {
+  if (!c) return;
+  for (void* p : c->staging)
+    if (p) (void)hipFree(p);
+  for (auto e : c->ev_filled) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_free) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_t0) if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_t1) if (e) (void)hipEventDestroy(e);
+  if (c->ev_tab_ing) (void)hipEventDestroy(c->ev_tab_ing);
+  if (c->ev_att) (void)hipEventDestroy(c->ev_att);
+  if (c->d_tab_ing) (void)hipFree(c->d_tab_ing);
+  if (c->h_tab_ing) (void)hipHostFree(c->h_tab_ing);
+  if (c->d_att) (void)hipFree(c->d_att);
+  if (c->h_att) (void)hipHostFree(c->h_att);
+  for (auto& s : c->s_copy) if (s) (void)hipStreamDestroy(s);
+  if (c->s_scatter) (void)hipStreamDestroy(c->s_scatter);
+  if (c->own_compute && c->s_compute) (void)hipStreamDestroy(c->s_compute);
+  (void)hipGetLastError();
+  delete c;
+}
+
+int validate_config(const calvo_config* cfg) {
+  if (!cfg) return fail(CALVO_EINVAL, "config is NULL");
+  if (cfg->n_layers <= 0) return fail(CALVO_EINVAL, "n_layers must be positive");
+  if (cfg->n_kv_heads <= 0 || cfg->n_q_heads <= 0 || cfg->n_q_heads % cfg->n_kv_heads != 0)
+    return fail(CALVO_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", cfg->n_q_heads,
+                cfg->n_kv_heads);
+  if (cfg->head_dim <= 0 || cfg->head_dim > 256 || cfg->head_dim % 8 != 0)
+    return fail(CALVO_EINVAL, "head_dim must be a multiple of 8 in [8, 256]");
+  if (cfg->block_tokens != kBlockTokens) return fail(CALVO_EINVAL, "block_tokens must be 16");
+  if (cfg->dtype != CALVO_BF16 && cfg->dtype != CALVO_F32) return fail(CALVO_EINVAL, "unknown dtype");
+  if (cfg->pool_blocks <= 0 || cfg->pool_blocks > INT32_MAX) return fail(CALVO_EINVAL, "pool_blocks out of range");
+  if (!cfg->pool) return fail(CALVO_EINVAL, "pool is NULL");
+  if (((uintptr_t)cfg->pool & 15) != 0) return fail(CALVO_EINVAL, "pool must be 16-byte aligned");
+  if (cfg->n_staging != 0 && (cfg->n_staging < 2 || cfg->n_staging > 8))
+    return fail(CALVO_EINVAL, "n_staging must be 0 or in [2, 8]");
+  if (cfg->n_copy_streams < 0 || cfg->n_copy_streams > 2) return fail(CALVO_EINVAL, "n_copy_streams must be 0, 1 or 2");
+  const size_t elt = cfg->dtype == CALVO_BF16 ? 2 : 4;
+  const size_t blk = (size_t)2 * kBlockTokens * cfg->n_kv_heads * cfg->head_dim * elt;
+  if (cfg->staging_bytes != 0 && cfg->staging_bytes < blk)
+    return fail(CALVO_EINVAL, "staging_bytes (%zu) is smaller than one block (%zu)", cfg->staging_bytes, blk);
+  return CALVO_OK;
+}
+
+// Checks shared by ingest and attention.  Nothing is queued before these pass.
+int validate_requests(const calvo_ctx* c, const calvo_request* reqs, int n_reqs, bool need_host,
+                      std::vector<char>& seen) {
+  if (!reqs && n_reqs > 0) return fail(CALVO_EINVAL, "reqs is NULL");
+  if (n_reqs < 0) return fail(CALVO_EINVAL, "n_reqs is negative");
+  for (int r = 0; r < n_reqs; r++) {
+    const calvo_request& q = reqs[r];
+    if (q.n_prefix_blocks < 0 || q.suffix_len < 0)
+      return fail(CALVO_EINVAL, "request %d: negative block or token count", r);
+    if (q.first_ingest_block < 0 || q.first_ingest_block > q.n_prefix_blocks)
+      return fail(CALVO_EINVAL, "request %d: first_ingest_block outside [0, n_prefix_blocks]", r);
+    const int64_t n_tab = (int64_t)q.n_prefix_blocks + (q.suffix_len + kBlockTokens - 1) / kBlockTokens;
+    if (n_tab > c->cfg.pool_blocks)
+      return fail(CALVO_ENOMEM, "request %d needs %lld slots, the pool has %lld", r, (long long)n_tab,
+                  (long long)c->cfg.pool_blocks);
+    if (n_tab > 0 && !q.block_table) return fail(CALVO_EINVAL, "request %d: block_table is NULL", r);
+    if ((int64_t)q.n_prefix_blocks * kBlockTokens + q.suffix_len > INT32_MAX)
+      return fail(CALVO_EINVAL, "request %d: context too long", r);
+    seen.assign((size_t)c->cfg.pool_blocks, 0);
+    for (int64_t j = 0; j < n_tab; j++) {
+      const int32_t s = q.block_table[j];
+      if (s < 0 || s >= c->cfg.pool_blocks)
+        return fail(CALVO_EINVAL, "request %d: slot %d at table[%lld] is outside the pool (not allocated)", r, s,
+                    (long long)j);
+      if (seen[s]) return fail(CALVO_EINVAL, "request %d: slot %d appears twice in its table", r, s);
+      seen[s] = 1;
+    }
+    if (need_host && q.n_prefix_blocks > q.first_ingest_block) {
+      if (!q.host_kv) return fail(CALVO_EINVAL, "request %d: host_kv is NULL", r);
+      if (((uintptr_t)q.host_kv & 15) != 0 || (q.host_layer_stride & 15) != 0)
+        return fail(CALVO_EINVAL, "request %d: host_kv and host_layer_stride must be 16-byte aligned", r);
+      if (c->cfg.n_layers > 1 && q.host_layer_stride < (int64_t)q.n_prefix_blocks * (int64_t)c->blk_bytes)
+        return fail(CALVO_EINVAL, "request %d: host_layer_stride is smaller than the request's blocks", r);
+    }
+  }
+  return CALVO_OK;
+}
+
+int ensure_ing_table(calvo_ctx* c, size_t n) {
+  if (n <= c->tab_ing_cap) return CALVO_OK;
+  if (c->tab_ing_pending) { HIP_TRY(hipEventSynchronize(c->ev_tab_ing)); c->tab_ing_pending = false; }
+  HIP_TRY(hipStreamSynchronize(c->s_scatter));
+  size_t cap = std::max<size_t>(n, 4096);
+  int32_t *d = nullptr, *h = nullptr;
+  HIP_TRY(hipMalloc((void**)&d, cap * 4));
+  hipError_t e = hipHostMalloc((void**)&h, cap * 4, hipHostMallocDefault);
+  if (e != hipSuccess) { (void)hipFree(d); return fail_hip(e, "hipHostMalloc(table shadow)"); }
+  if (c->d_tab_ing) (void)hipFree(c->d_tab_ing);
+  if (c->h_tab_ing) (void)hipHostFree(c->h_tab_ing);
+  c->d_tab_ing = d; c->h_tab_ing = h; c->tab_ing_cap = cap;
+  return CALVO_OK;
+}
+
+int ensure_att_blob(calvo_ctx* c, size_t n) {
+  if (n <= c->att_cap) return CALVO_OK;
+  if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
+  HIP_TRY(hipStreamSynchronize(c->s_compute));
+  size_t cap = std::max<size_t>(n, 8192);
+  int32_t *d = nullptr, *h = nullptr;
+  HIP_TRY(hipMalloc((void**)&d, cap * 4));
+  hipError_t e = hipHostMalloc((void**)&h, cap * 4, hipHostMallocDefault);
+  if (e != hipSuccess) { (void)hipFree(d); return fail_hip(e, "hipHostMalloc(descriptor shadow)"); }
+  if (c->d_att) (void)hipFree(c->d_att);
+  if (c->h_att) (void)hipHostFree(c->h_att);
+  c->d_att = d; c->h_att = h; c->att_cap = cap; c->att_len = 0;
+  return CALVO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* calvo_last_error(void) { return g_err.c_str(); }
+
+int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
+  if (!out) return fail(CALVO_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = validate_config(cfg);
+  if (rc != CALVO_OK) return rc;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  calvo_ctx* c = new (std::nothrow) calvo_ctx();
+  if (!c) return fail(CALVO_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->elt = cfg->dtype == CALVO_BF16 ? 2 : 4;
+  c->blk_bytes = (size_t)2 * kBlockTokens * cfg->n_kv_heads * cfg->head_dim * c->elt;
+  c->layer_bytes = (int64_t)cfg->pool_blocks * (int64_t)c->blk_bytes;
+  c->n_staging = cfg->staging_bytes ? (cfg->n_staging ? cfg->n_staging : 2) : 0;
+  c->n_copy = cfg->n_copy_streams ? cfg->n_copy_streams : 1;
+  c->staging_blocks = cfg->staging_bytes / c->blk_bytes;
+
+#define CREATE_TRY(expr)                                                        \
+  do {                                                                          \
+    hipError_t e_ = (expr);                                                     \
+    if (e_ != hipSuccess) { int rc_ = fail_hip(e_, #expr); destroy_partial(c); return rc_; } \
+  } while (0)
+
+  for (int i = 0; i < c->n_copy; i++) CREATE_TRY(hipStreamCreateWithFlags(&c->s_copy[i], hipStreamNonBlocking));
+  CREATE_TRY(hipStreamCreateWithFlags(&c->s_scatter, hipStreamNonBlocking));
+  if (cfg->compute_stream) {
+    c->s_compute = (hipStream_t)cfg->compute_stream;
+  } else {
+    CREATE_TRY(hipStreamCreateWithFlags(&c->s_compute, hipStreamNonBlocking));
+    c->own_compute = true;
+  }
+  c->staging.assign(c->n_staging, nullptr);
+  c->ev_filled.assign(c->n_staging, nullptr);
+  c->ev_free.assign(c->n_staging, nullptr);
+  c->free_recorded.assign(c->n_staging, 0);
+  for (int i = 0; i < c->n_staging; i++) {
+    CREATE_TRY(hipMalloc(&c->staging[i], (size_t)c->staging_blocks * c->blk_bytes));
+    CREATE_TRY(hipEventCreateWithFlags(&c->ev_filled[i], hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
+  }
+  c->ev_layer.assign(cfg->n_layers, nullptr);
+  c->ev_t0.assign(cfg->n_layers, nullptr);
+  c->ev_t1.assign(cfg->n_layers, nullptr);
+  c->layer_issued.assign(cfg->n_layers, 0);
+  c->timed.assign(cfg->n_layers, 0);
+  for (int l = 0; l < cfg->n_layers; l++) {
+    CREATE_TRY(hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming));
+    CREATE_TRY(hipEventCreate(&c->ev_t0[l]));
+    CREATE_TRY(hipEventCreate(&c->ev_t1[l]));
+  }
+  CREATE_TRY(hipEventCreateWithFlags(&c->ev_tab_ing, hipEventDisableTiming));
+  CREATE_TRY(hipEventCreateWithFlags(&c->ev_att, hipEventDisableTiming));
+#undef CREATE_TRY
+  *out = c;
+  return CALVO_OK;
+}
+
+int calvo_destroy(calvo_ctx* c) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  hipError_t e = hipSuccess, t;
+  for (auto& s : c->s_copy)
+    if (s && (t = hipStreamSynchronize(s)) != hipSuccess) e = t;
+  if (c->s_scatter && (t = hipStreamSynchronize(c->s_scatter)) != hipSuccess) e = t;
+  if (c->s_compute && (t = hipStreamSynchronize(c->s_compute)) != hipSuccess) e = t;
+  destroy_partial(c);
+  if (e != hipSuccess) return fail_hip(e, "synchronize at destroy");
+  return CALVO_OK;
+}
+
+int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer_begin < 0 || layer_end > c->cfg.n_layers || layer_begin > layer_end)
+    return fail(CALVO_EINVAL, "layer range [%d, %d) outside [0, %d]", layer_begin, layer_end, c->cfg.n_layers);
+  std::vector<char> seen;
+  int rc = validate_requests(c, reqs, n_reqs, true, seen);
+  if (rc != CALVO_OK) return rc;
+
+  // the source must be page-locked host memory the device can address
+  std::vector<const unsigned char*> src(n_reqs, nullptr);
+  std::vector<size_t> tab_off(n_reqs, 0);
+  size_t n_tab = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    tab_off[r] = n_tab;
+    n_tab += (size_t)reqs[r].n_prefix_blocks;
+    if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) continue;
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, reqs[r].host_kv);
+    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+      (void)hipGetLastError();
+      return fail(CALVO_EINVAL, "request %d: host_kv is not page-locked host memory", r);
+    }
+    void* dp = const_cast<void*>(reqs[r].host_kv);
+    if (c->n_staging == 0) {
+      dp = nullptr;
+      e = hipHostGetDevicePointer(&dp, const_cast<void*>(reqs[r].host_kv), 0);
+      if (e != hipSuccess || !dp) {
+        (void)hipGetLastError();
+        return fail(CALVO_EINVAL, "request %d: host_kv has no device mapping", r);
+      }
+    }
+    src[r] = (const unsigned char*)dp;
+  }
+  if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
+
+  // block tables -> device (ingest stream)
+  if (n_tab > 0) {
+    rc = ensure_ing_table(c, n_tab);
+    if (rc != CALVO_OK) return rc;
+    if (c->tab_ing_pending) { HIP_TRY(hipEventSynchronize(c->ev_tab_ing)); c->tab_ing_pending = false; }
+    for (int r = 0; r < n_reqs; r++)
+      if (reqs[r].n_prefix_blocks)
+        memcpy(c->h_tab_ing + tab_off[r], reqs[r].block_table, (size_t)reqs[r].n_prefix_blocks * 4);
+    HIP_TRY(hipMemcpyAsync(c->d_tab_ing, c->h_tab_ing, n_tab * 4, hipMemcpyHostToDevice, c->s_scatter));
+    HIP_TRY(hipEventRecord(c->ev_tab_ing, c->s_scatter));
+    c->tab_ing_pending = true;
+  }
+
+  for (int l = layer_begin; l < layer_end; l++) {
+    unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
+    for (int r = 0; r < n_reqs; r++) {
+      const calvo_request& q = reqs[r];
+      const int64_t first = q.first_ingest_block, nblk = q.n_prefix_blocks;
+      if (nblk == first) continue;
+      const unsigned char* lsrc = src[r] + (int64_t)l * q.host_layer_stride;
+      if (c->n_staging == 0) {
+        // zero-copy: the scatter kernel reads the pinned blocks over PCIe itself
+        HIP_TRY(launch_scatter_blocks(lsrc + first * (int64_t)c->blk_bytes, pool_layer,
+                                      c->d_tab_ing + tab_off[r] + first, nblk - first, (int32_t)c->blk_bytes,
+                                      c->scatter_grid, c->s_scatter));
+      } else {
+        for (int64_t j0 = first; j0 < nblk; j0 += c->staging_blocks) {
+          const int64_t nb = std::min<int64_t>(c->staging_blocks, nblk - j0);
+          const int b = (int)(c->seq % (uint64_t)c->n_staging);
+          hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
+          if (c->free_recorded[b]) HIP_TRY(hipStreamWaitEvent(cs, c->ev_free[b], 0));
+          HIP_TRY(hipMemcpyAsync(c->staging[b], lsrc + j0 * (int64_t)c->blk_bytes, (size_t)nb * c->blk_bytes,
+                                 hipMemcpyHostToDevice, cs));
+          HIP_TRY(hipEventRecord(c->ev_filled[b], cs));
+          HIP_TRY(hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0));
+          HIP_TRY(launch_scatter_blocks(c->staging[b], pool_layer, c->d_tab_ing + tab_off[r] + j0, nb,
+                                        (int32_t)c->blk_bytes, 1024, c->s_scatter));
+          HIP_TRY(hipEventRecord(c->ev_free[b], c->s_scatter));
+          c->free_recorded[b] = 1;
+          c->seq++;
+        }
+      }
+    }
+    HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
+    c->layer_issued[l] = 1;
+  }
+  return CALVO_OK;
+}
+
+int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  if (mode != CALVO_EV_QUERY && mode != CALVO_EV_HOST_WAIT && mode != CALVO_EV_STREAM_WAIT)
+    return fail(CALVO_EINVAL, "unknown mode %d", mode);
+  if (!c->layer_issued[layer]) return CALVO_OK;
+  if (mode == CALVO_EV_QUERY) {
+    hipError_t e = hipEventQuery(c->ev_layer[layer]);
+    if (e == hipSuccess) return CALVO_OK;
+    if (e == hipErrorNotReady) { (void)hipGetLastError(); return fail(CALVO_ENOTREADY, "layer %d is still loading", layer); }
+    return fail_hip(e, "hipEventQuery");
+  }
+  if (mode == CALVO_EV_HOST_WAIT) {
+    HIP_TRY(hipEventSynchronize(c->ev_layer[layer]));
+    return CALVO_OK;
+  }
+  hipStream_t s = stream ? (hipStream_t)stream : c->s_compute;
+  HIP_TRY(hipStreamWaitEvent(s, c->ev_layer[layer], 0));
+  return CALVO_OK;
+}
+
+int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
+                       const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  std::vector<char> seen;
+  int rc = validate_requests(c, reqs, n_reqs, false, seen);
+  if (rc != CALVO_OK) return rc;
+  if (n_reqs > 0 && !cu_suffix) return fail(CALVO_EINVAL, "cu_suffix is NULL");
+  if (n_reqs > 0 && cu_suffix[0] != 0) return fail(CALVO_EINVAL, "cu_suffix[0] must be 0");
+  for (int r = 0; r < n_reqs; r++)
+    if (cu_suffix[r + 1] - cu_suffix[r] != reqs[r].suffix_len)
+      return fail(CALVO_EINVAL, "cu_suffix[%d+1]-cu_suffix[%d] != suffix_len of request %d", r, r, r);
+  const int total = n_reqs > 0 ? cu_suffix[n_reqs] : 0;
+  if ((k_suffix == nullptr) != (v_suffix == nullptr))
+    return fail(CALVO_EINVAL, "k_suffix and v_suffix must both be given or both be NULL");
+  if (total > 0) {
+    if (!q || !out) return fail(CALVO_EINVAL, "q or out is NULL");
+    if ((((uintptr_t)q | (uintptr_t)out | (uintptr_t)k_suffix | (uintptr_t)v_suffix) & 15) != 0)
+      return fail(CALVO_EINVAL, "q, out, k_suffix and v_suffix must be 16-byte aligned");
+  }
+  if (total == 0) {
+    // nothing to compute; still order the compute stream after the layer's ingest
+    if (c->layer_issued[layer]) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+    return CALVO_OK;
+  }
+
+  const calvo_config& cf = c->cfg;
+  const int G = cf.n_q_heads / cf.n_kv_heads;
+  const bool mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
+  const int HW = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  const int tile_tokens = mfma ? attn_mfma_tile_tokens(HW) : 1;
+
+  // ---- descriptor blob: requests, work items (heaviest first), tables
+  std::vector<int32_t> blob;
+  blob.reserve(4 * n_reqs + 1024);
+  size_t n_tab = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
+    blob.push_back((int32_t)n_tab);
+    blob.push_back(reqs[r].n_prefix_blocks * kBlockTokens);
+    blob.push_back(reqs[r].suffix_len);
+    blob.push_back(cu_suffix[r]);
+    n_tab += (size_t)nt;
+  }
+  struct Item { int32_t req, tile; int64_t cost; };
+  std::vector<Item> items;
+  if (mfma) {
+    for (int r = 0; r < n_reqs; r++) {
+      const int nt = (reqs[r].suffix_len + tile_tokens - 1) / tile_tokens;
+      for (int t = 0; t < nt; t++)
+        items.push_back({r, t, (int64_t)reqs[r].n_prefix_blocks * kBlockTokens +
+                                   std::min<int64_t>((int64_t)(t + 1) * tile_tokens, reqs[r].suffix_len)});
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
+  }
+  const size_t items_off = blob.size();
+  for (const Item& it : items) { blob.push_back(it.req); blob.push_back(it.tile); }
+  const size_t tables_off = blob.size();
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
+    blob.insert(blob.end(), reqs[r].block_table, reqs[r].block_table + nt);
+  }
+
+  rc = ensure_att_blob(c, blob.size());
+  if (rc != CALVO_OK) return rc;
+  const bool same = c->att_len == blob.size() && memcmp(c->h_att, blob.data(), blob.size() * 4) == 0;
+  if (!same) {
+    if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
+    memcpy(c->h_att, blob.data(), blob.size() * 4);
+    c->att_len = blob.size();
+    HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att, blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+    HIP_TRY(hipEventRecord(c->ev_att, c->s_compute));
+    c->att_pending = true;
+  }
+
+  if (c->layer_issued[layer]) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+
+  unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
+  const ReqDesc* d_reqs = (const ReqDesc*)c->d_att;
+  const int32_t* d_tables = c->d_att + tables_off;
+
+  if (k_suffix) {
+    AppendParams ap{};
+    ap.k_suffix = k_suffix; ap.v_suffix = v_suffix; ap.pool_layer = pool_layer;
+    ap.reqs = d_reqs; ap.tables = d_tables; ap.n_reqs = n_reqs; ap.total_tokens = total;
+    ap.row_chunks = (int32_t)((size_t)cf.n_kv_heads * cf.head_dim * c->elt / 16);
+    HIP_TRY(launch_suffix_append(ap, c->s_compute));
+  }
+
+  AttnParams p{};
+  p.q = q; p.out = out; p.pool_layer = pool_layer;
+  p.reqs = d_reqs; p.items = (const WorkItem*)(c->d_att + items_off); p.tables = d_tables;
+  p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
+  p.heads_per_wg = HW; p.tile_tokens = tile_tokens;
+  p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
+  HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
+  if (mfma) {
+    p.n_items = (int32_t)items.size();
+    HIP_TRY(launch_attn_mfma(p, c->s_compute));
+  } else {
+    p.n_items = n_reqs;
+    HIP_TRY(launch_attn_simple(p, cf.dtype, total, c->s_compute));
+  }
+  HIP_TRY(hipEventRecord(c->ev_t1[layer], c->s_compute));
+  c->timed[layer] = 1;
+  return CALVO_OK;
+}
+
+int calvo_attn_kernel_ms(calvo_ctx* c, int layer, float* ms) {
+  if (!c || !ms) return fail(CALVO_EINVAL, "NULL argument");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  if (!c->timed[layer]) return fail(CALVO_ENOTREADY, "no attention kernel was queued for layer %d", layer);
+  HIP_TRY(hipEventSynchronize(c->ev_t1[layer]));
+  HIP_TRY(hipEventElapsedTime(ms, c->ev_t0[layer], c->ev_t1[layer]));
+  return CALVO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Internal declarations shared by the host API and the HIP kernels of libcalvo.
+// Not part of the public ABI (see include/calvo.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace calvo {
+
+// One request as the attention kernels see it (int32 x 4, device memory).
+struct ReqDesc {
+  int32_t table_off;  // offset of this request's block table inside the table array
+  int32_t prefix_len; // P (tokens)
+  int32_t suffix_len; // S (tokens)
+  int32_t q_off;      // first row of this request inside q / out / k_suffix / v_suffix
+};
+
+// One unit of attention work: a tile of suffix tokens of one request.
+struct WorkItem {
+  int32_t req;
+  int32_t q_tile;     // tile index inside the request's suffix
+};
+
+struct AttnParams {
+  const void* q;
+  void* out;
+  const void* pool_layer;   // this layer's [pool_blocks][2][B][Hkv][D]
+  const ReqDesc* reqs;
+  const WorkItem* items;
+  const int32_t* tables;
+  int32_t n_items;          // tiles over all requests
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
+  int32_t tile_tokens;      // suffix tokens per work item
+  float scale;              // softmax scale (natural-exponent units)
+};
+
+struct AppendParams {
+  const void* k_suffix;
+  const void* v_suffix;
+  void* pool_layer;
+  const ReqDesc* reqs;
+  const int32_t* tables;
+  int32_t n_reqs;
+  int32_t total_tokens;
+  int32_t row_chunks;       // 16-byte chunks in one token's K (or V) row: Hkv*D*elt/16
+};
+
+// Scatter n_blocks consecutive source blocks to the pool slots table[0..n_blocks).
+hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_t* table, int64_t n_blocks,
+                                 int32_t blk_bytes, int grid, hipStream_t stream);
+hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
+hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
+hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
+int attn_mfma_tile_tokens(int heads_per_wg);
+
+constexpr int kBlockTokens = 16;
+
+}  // namespace calvo

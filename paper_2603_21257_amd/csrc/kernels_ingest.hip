@@ -1,0 +1,84 @@
+// Byte-moving kernels of the L2->L1 loading stage (paper Section 3.1) and of the
+// suffix KV write of prefill (Section 2.1).  gfx950 only.
+//
+// scatter_blocks: source blocks are consecutive (a host staging area read over
+// PCIe, or a device staging buffer filled by the copy engine); block j goes to
+// pool slot table[j].  The grid walks the source linearly in 16-byte units so the
+// PCIe / HBM read stream is sequential; every lane keeps four loads in flight.
+// A few workgroups saturate the host link, so the grid is kept small and the
+// remaining compute units stay free for attention.
+#include "calvo_internal.h"
+
+namespace calvo {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__global__ void __launch_bounds__(256)
+scatter_blocks_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ pool_layer,
+                      const int32_t* __restrict__ table, int64_t n_chunks, int32_t chunks_per_block) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n_chunks; i += 4 * stride) {
+    u32x4 v[4];
+    int64_t dst[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t c = i + u * stride;
+      v[u] = __builtin_nontemporal_load(src + c);
+      const int64_t j = c / chunks_per_block;
+      dst[u] = (int64_t)table[j] * chunks_per_block + (c - j * chunks_per_block);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) pool_layer[dst[u]] = v[u];
+  }
+  for (; i < n_chunks; i += stride) {
+    const int64_t j = i / chunks_per_block;
+    pool_layer[(int64_t)table[j] * chunks_per_block + (i - j * chunks_per_block)] = __builtin_nontemporal_load(src + i);
+  }
+}
+
+hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_t* table, int64_t n_blocks,
+                                 int32_t blk_bytes, int grid, hipStream_t stream) {
+  if (n_blocks <= 0) return hipSuccess;
+  const int32_t cpb = blk_bytes / 16;
+  const int64_t n_chunks = n_blocks * cpb;
+  int64_t need = (n_chunks + 255) / 256;
+  if (grid > need) grid = (int)need;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(scatter_blocks_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4*)src,
+                     (u32x4*)pool_layer, table, n_chunks, cpb);
+  return hipGetLastError();
+}
+
+// Suffix token i of request r sits at absolute position P_r + i: slot table_r[pos / 16],
+// row pos % 16 of the K half and of the V half.  One lane per 16-byte chunk of a row.
+__global__ void __launch_bounds__(256) suffix_append_kernel(AppendParams p) {
+  const int64_t n = (int64_t)p.total_tokens * p.row_chunks;
+  const int64_t half_chunks = (int64_t)kBlockTokens * p.row_chunks;   // one K (or V) half of a block
+  const u32x4* ks = (const u32x4*)p.k_suffix;
+  const u32x4* vs = (const u32x4*)p.v_suffix;
+  u32x4* pool = (u32x4*)p.pool_layer;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int32_t tok = (int32_t)(i / p.row_chunks);
+    const int32_t c = (int32_t)(i - (int64_t)tok * p.row_chunks);
+    int r = 0;
+    while (r + 1 < p.n_reqs && tok >= p.reqs[r + 1].q_off) r++;
+    const ReqDesc rd = p.reqs[r];
+    const int32_t pos = rd.prefix_len + (tok - rd.q_off);
+    const int64_t slot = p.tables[rd.table_off + pos / kBlockTokens];
+    const int64_t base = slot * 2 * half_chunks + (int64_t)(pos % kBlockTokens) * p.row_chunks + c;
+    pool[base] = ks[i];
+    pool[base + half_chunks] = vs[i];
+  }
+}
+
+hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream) {
+  const int64_t n = (int64_t)p.total_tokens * p.row_chunks;
+  if (n <= 0) return hipSuccess;
+  int grid = (int)((n + 255) / 256);
+  if (grid > 2048) grid = 2048;
+  hipLaunchKernelGGL(suffix_append_kernel, dim3(grid), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace calvo

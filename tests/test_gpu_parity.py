@@ -1,0 +1,209 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Sizes are small enough for the full oracle yet span several 64-key tiles, several query
+tiles, ragged tails and partial last blocks.  Pool bytes must be bit exact (including every
+slot the path must not touch); attention must meet the stated tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import hip_harness as hh
+from paper_2603_21257_amd import binding as cb
+from paper_2603_21257_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def check(w, **kw):
+    print(f"[case] {w.name} shape={w.shape} lens={[(r.prefix_len, r.suffix_len) for r in w.requests]} kw={kw}",
+          flush=True)
+    pool_g, out_g = hh.run_hip(w, **kw)
+    pool_o, out_o = hh.run_oracle(w, scale=kw.get("scale") or None)
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    return hh.assert_attn_close(out_g, out_o, w.shape.dtype)
+
+
+def test_config1_fp32_full():
+    """BASELINE config 1 in full: fp32, 8Q/2KV heads, D=64, P=1024, S=128, pool of 256 slots."""
+    w = wl.make_config(1)
+    mx, mean = check(w)
+    print(f"cfg1 fp32 max {mx:.2e} mean {mean:.2e}")
+
+
+@pytest.mark.parametrize("P,S", [(160, 77), (0, 130), (1024, 64), (48, 1), (256, 200)])
+def test_bf16_mfma_single_request(P, S):
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 128)
+    w = wl.make_custom(shape, [(P, S)], seed=100 + P + S)
+    check(w)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2), (6, 2), (12, 4)])
+def test_bf16_mfma_gqa_group_sizes(Hq, Hkv):
+    shape = wl.Shape(1, Hq, Hkv, 128, "bf16", 64)
+    w = wl.make_custom(shape, [(192, 150)], seed=7 * Hq + Hkv)
+    check(w)
+
+
+def test_bf16_mfma_varlen_batch_with_shared_run():
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 256)
+    w = wl.make_custom(shape, [(256, 90), (128, 257), (512, 33), (64, 0), (128, 64)], seed=5, shared_blocks=4)
+    check(w)
+
+
+def test_bf16_generic_kernel_other_head_dims():
+    for D in (64, 96, 256):
+        shape = wl.Shape(1, 4, 2, D, "bf16", 64)
+        w = wl.make_custom(shape, [(96, 70)], seed=D)
+        check(w)
+
+
+def test_fp32_varlen_and_explicit_scale():
+    shape = wl.Shape(2, 6, 3, 40, "f32", 64)
+    w = wl.make_custom(shape, [(64, 37), (0, 50), (160, 5)], seed=17)
+    check(w, scale=0.2)
+
+
+@pytest.mark.parametrize("staging_blocks,n_staging,n_copy", [(1, 2, 1), (3, 2, 2), (5, 4, 1), (64, 2, 1)])
+def test_staged_copy_engine_ingest_is_bit_exact(staging_blocks, n_staging, n_copy):
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 128)
+    w = wl.make_custom(shape, [(17 * 16, 40), (9 * 16, 20)], seed=23, shared_blocks=2)
+    check(w, staging_bytes=staging_blocks * shape.blk_bytes, n_staging=n_staging, n_copy_streams=n_copy)
+
+
+def test_no_suffix_and_no_prefix_edge_cases():
+    shape = wl.Shape(1, 8, 2, 128, "bf16", 64)
+    w = wl.make_custom(shape, [(128, 0)], seed=3)           # nothing to compute: ingest only
+    pool_g, out_g = hh.run_hip(w)
+    pool_o, _ = hh.run_oracle(w, attn=False)
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    assert out_g.size == 0
+    w = wl.make_custom(shape, [(0, 1)], seed=4)             # single token, no hit: O = V[0]
+    pool_g, out_g = hh.run_hip(w)
+    pool_o, out_o = hh.run_oracle(w)
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    assert np.array_equal(hh.orc.widen(out_g)[0, 0, :, :],
+                          np.repeat(hh.orc.widen(w.v_suffix[0, 0]), shape.group, axis=0))
+
+
+def test_permuted_block_table_gives_same_output_bits():
+    """Moving the same KV to other slots must not change a single output bit on the GPU either."""
+    shape = wl.Shape(1, 8, 2, 128, "bf16", 96)
+    w = wl.make_custom(shape, [(320, 100)], seed=31)
+    _, out_a = hh.run_hip(w)
+    rng = np.random.default_rng(1)
+    w.requests[0].table = rng.permutation(shape.pool_blocks)[:len(w.requests[0].table)].astype(np.int32)
+    _, out_b = hh.run_hip(w)
+    assert np.array_equal(out_a, out_b)
+
+
+def test_prefix_hit_equals_full_recompute_on_gpu():
+    """Same tokens served as (P=256 hit, S=96) and as (P=0, S=352): suffix rows agree within tolerance."""
+    shape = wl.Shape(1, 8, 2, 128, "bf16", 64)
+    w_hit = wl.make_custom(shape, [(256, 96)], seed=41)
+    _, out_hit = hh.run_hip(w_hit)
+    B, r = 16, w_hit.requests[0]
+    # rebuild the same sequence as one no-hit request: K/V of the prefix come from the host blocks
+    blocks = w_hit.host_kv[0].reshape(16, 2, B, 2, 128)
+    k_pre = blocks[:, 0].reshape(256, 2, 128)
+    v_pre = blocks[:, 1].reshape(256, 2, 128)
+    w_full = wl.make_custom(shape, [(0, 352)], seed=42)
+    w_full.k_suffix = np.concatenate([k_pre, w_hit.k_suffix[0]])[None]
+    w_full.v_suffix = np.concatenate([v_pre, w_hit.v_suffix[0]])[None]
+    qf = w_full.q.copy()
+    qf[0, 256:] = w_hit.q[0]
+    w_full.q = qf
+    _, out_full = hh.run_hip(w_full)
+    a = hh.orc.widen(out_hit[0])
+    b = hh.orc.widen(out_full[0, 256:])
+    assert np.abs(a - b).max() <= 2e-2
+    # and both equal the oracle of the hit formulation
+    _, out_o = hh.run_oracle(w_hit)
+    hh.assert_attn_close(out_full[:, 256:], out_o, "bf16")
+
+
+def test_layer_events_and_layer_ranges():
+    shape = wl.Shape(4, 8, 2, 128, "bf16", 64)
+    w = wl.make_custom(shape, [(256, 16)], seed=51)
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(shape), shape, dev)
+    host = hh.to_torch(w.host_kv, shape, pin=True)
+    ctx = cb.calvo_create(4, 8, 2, 128, cb.CALVO_BF16, 64, pool)
+    try:
+        reqs = hh.make_requests(w, host)
+        assert cb.calvo_layer_event(ctx, 2, cb.CALVO_EV_QUERY)          # never ingested: ready
+        cb.calvo_kv_ingest(ctx, reqs, 1, 3)
+        assert cb.calvo_layer_event(ctx, 1, cb.CALVO_EV_HOST_WAIT)
+        assert cb.calvo_layer_event(ctx, 2, cb.CALVO_EV_HOST_WAIT)
+        assert cb.calvo_layer_event(ctx, 2, cb.CALVO_EV_QUERY)
+        s = torch.cuda.Stream()
+        assert cb.calvo_layer_event(ctx, 2, cb.CALVO_EV_STREAM_WAIT, s.cuda_stream)
+        s.synchronize()
+    finally:
+        cb.calvo_destroy(ctx)
+    got = hh.to_numpy_stored(pool, shape)
+    want = hh.sentinel_pool_np(shape)
+    r = w.requests[0]
+    hh.orc.kv_ingest(want, w.host_kv, r.table, r.n_prefix_blocks, layer_begin=1, layer_end=3)
+    hh.assert_pool_bit_exact(got, want)                                  # layers 0 and 3 untouched
+
+
+def test_invalid_requests_write_nothing():
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 32)
+    w = wl.make_custom(shape, [(128, 16)], seed=61)
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(shape), shape, dev)
+    host = hh.to_torch(w.host_kv, shape, pin=True)
+    ctx = cb.calvo_create(2, 8, 2, 128, cb.CALVO_BF16, 32, pool)
+    try:
+        r = w.requests[0]
+        stride = w.host_blocks * shape.blk_bytes
+        bad = r.table.copy(); bad[3] = 32                               # destination not allocated
+        dup = r.table.copy(); dup[5] = dup[1]
+        pageable = np.zeros(w.host_kv.size, np.uint16)
+        cases = [
+            ([cb.make_request(host, stride, bad, r.n_prefix_blocks, r.suffix_len)], 0, 2),
+            ([cb.make_request(host, stride, dup, r.n_prefix_blocks, r.suffix_len)], 0, 2),
+            ([cb.make_request(host, stride, r.table, r.n_prefix_blocks, r.suffix_len)], 0, 3),
+            ([cb.make_request(host, stride, r.table, r.n_prefix_blocks, r.suffix_len, first_ingest_block=9)], 0, 2),
+            ([cb.make_request(None, stride, r.table, r.n_prefix_blocks, r.suffix_len)], 0, 2),
+            ([cb.make_request(pageable.ctypes.data, stride, r.table, r.n_prefix_blocks, r.suffix_len)], 0, 2),
+            ([cb.make_request(host, 16, r.table, r.n_prefix_blocks, r.suffix_len)], 0, 2),
+        ]
+        for reqs, lb, le in cases:
+            with pytest.raises(cb.CalvoError) as ei:
+                cb.calvo_kv_ingest(ctx, reqs, lb, le)
+            assert ei.value.code == cb.CALVO_EINVAL, ei.value
+        big = np.arange(40, dtype=np.int32)
+        with pytest.raises(cb.CalvoError) as ei:
+            cb.calvo_kv_ingest(ctx, [cb.make_request(host, stride, big, 40, 0)], 0, 2)
+        assert ei.value.code == cb.CALVO_ENOMEM
+        q = torch.zeros(16, 8, 128, dtype=torch.bfloat16, device=dev)
+        with pytest.raises(cb.CalvoError):
+            cb.calvo_prefill_attn(ctx, 0, q, None, None, q.clone(),
+                                  [cb.make_request(host, stride, r.table, r.n_prefix_blocks, r.suffix_len)],
+                                  np.array([0, 15], np.int32))
+        with pytest.raises(cb.CalvoError):
+            cb.calvo_prefill_attn(ctx, 5, q, None, None, q.clone(),
+                                  [cb.make_request(host, stride, r.table, r.n_prefix_blocks, r.suffix_len)],
+                                  np.array([0, 16], np.int32))
+    finally:
+        cb.calvo_destroy(ctx)
+    hh.assert_pool_bit_exact(hh.to_numpy_stored(pool, shape), hh.sentinel_pool_np(shape))
+
+
+def test_attention_waits_for_ingest_of_its_layer():
+    """Compute must see fully loaded bytes even when it is queued right behind a long ingest:
+    a large prefix in a NaN-poisoned pool, attention queued immediately, no host wait in between."""
+    shape = wl.Shape(6, 8, 2, 128, "bf16", 1200)
+    w = wl.make_custom(shape, [(1024 * 16, 32)], seed=71)              # 6 x 16 MiB to load
+    pool_g, out_g = hh.run_hip(w)
+    rows = [0, 15, 16, 31]
+    B = 16
+    pool_o, _ = hh.run_oracle(w, attn=False)
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    view = pool_o.reshape(6, 1200, 2, B, 2, 128)
+    r = w.requests[0]
+    for l in (0, 5):
+        want = hh.orc.prefill_attn_sampled(view[l], w.q[l], r.table, r.prefix_len, r.suffix_len, B, rows)
+        hh.assert_attn_close(out_g[l][rows], want, "bf16")

@@ -283,3 +283,15 @@ def test_batch_is_concatenation_of_requests():
     k0, _ = orc.gather_kv(pool, w.requests[0].table, 8, 0, 4)
     k1, _ = orc.gather_kv(pool, w.requests[1].table, 8, 0, 4)
     assert np.array_equal(k0, k1)
+
+
+def test_matrix_form_equals_row_form():
+    shape, req, q, k, v = tiny(91, P=48, S=21, Hq=4, Hkv=2, D=16, B=16, pool_blocks=32)
+    pool = build_pool(shape, req, k, v)
+    rows = [0, 1, 7, 15, 16, 20]
+    a = orc.prefill_attn(pool, q, req.table, 48, 21, 16, rows=rows)
+    b = orc.prefill_attn_sampled(pool, q, req.table, 48, 21, 16, rows)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-14)
+    # and against the brute-force loops directly
+    want = brute_force(q, k, v, 48, float(np.float32(1.0) / np.sqrt(np.float32(16))))
+    np.testing.assert_allclose(b, want[rows], rtol=0, atol=1e-13)
