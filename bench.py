@@ -40,7 +40,10 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload recipe 1..5 (default 3: 64K context)")
-    ap.add_argument("--staging-mib", type=int, default=0, help="0 = zero-copy ingest, else staged copy-engine ingest")
+    ap.add_argument("--staging-mib", type=int, default=64,
+                    help="size of each device staging buffer of the copy-engine ingest; 0 = zero-copy kernel ingest")
+    ap.add_argument("--mode", choices=["full", "attn", "ingest"], default="full",
+                    help="attn / ingest: run only that stage `steps` times (for profiling); no JSON contract line")
     ap.add_argument("--n-staging", type=int, default=0)
     ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -126,6 +129,15 @@ def main():
 
     try:
         poison()
+        if args.mode != "full":
+            fn = attn_only if args.mode == "attn" else ingest_only
+            if args.mode == "attn":
+                ingest_only()                      # attention needs a resident prefix
+            for _ in range(args.warmup):
+                fn()
+            t = [timed(fn) for _ in range(args.steps)]
+            log(f"[bench] mode {args.mode}: {statistics.mean(t):.3f} ms per pass over {L} layers")
+            return
         for _ in range(args.warmup):
             step()
         # ---- stage times in isolation (context for the overlap figure)

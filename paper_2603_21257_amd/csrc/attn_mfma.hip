@@ -2,10 +2,12 @@
 // bf16 MFMA (v_mfma_f32_32x32x16_bf16) for both contractions, fp32 online softmax.
 //
 // Work decomposition
-//   workgroup = 4 wavefronts = one tile of suffix tokens x up to 4 query heads that share
-//   one KV head; the K/V tile it streams is staged once in LDS and used by all 4 waves.
+//   workgroup = NW wavefronts = one tile of suffix tokens x up to 4 query heads that share
+//   one KV head; the 64-key K/V tile it streams is staged once in LDS and used by all waves.
 //   Each wave owns NT*32 query rows (one head) and keeps their Q, O and softmax state in
-//   registers for the whole key loop.
+//   registers for the whole key loop.  Default: NW=4, NT=1, two workgroups per CU, so each
+//   SIMD holds two waves of different workgroups and one wave's softmax (vector ALU) runs
+//   under the other's MFMAs.
 //
 // Transposed formulation (so that every softmax statistic is lane-local):
 //   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile (LDS, d-contiguous), B = Q (registers)
@@ -19,8 +21,13 @@
 //   LDS transpose read ds_read_b64_tr_b16: inside a 16-lane group, lane i receives element
 //   i%4 of the four 8-byte rows addressed by lanes i/4, i/4+4, i/4+8, i/4+12.
 //
-// LDS: two buffers of (K 64x128 + V 64x128) bf16, 16-byte chunks XOR-swizzled so that the
-// operand reads (K: 16 consecutive rows, same chunk; V: 4 rows x 64 bytes) hit distinct banks.
+// LDS: two buffers of (K 64 rows x 272 B, V 64 rows x 320 B).  The row padding makes the
+// operand reads conflict-free (K: 16 consecutive rows, same 16-byte column -> 16 distinct bank
+// quads; V: 4 rows x 64 bytes -> 4 distinct bank sixteenths) while every operand address is
+// one lane-constant base plus a compile-time offset, so the key loop spends no vector ALU
+// instruction on addressing.
+#include <stdlib.h>
+
 #include "calvo_internal.h"
 
 namespace calvo {
@@ -33,17 +40,36 @@ typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-constexpr int kD = 128;          // head_dim
-constexpr int kKT = 64;          // keys per LDS tile
-constexpr int kRowB = kD * 2;    // bytes per token row of one head
-constexpr int kTileB = kKT * kRowB;          // 16 KiB
-constexpr int kLdsBytes = 2 * 2 * kTileB;    // double-buffered K and V
+constexpr int kD = 128;                       // head_dim
+constexpr int kKT = 64;                       // keys per LDS tile
+constexpr int kKRow = 272;                    // padded K row stride in LDS (bytes)
+constexpr int kVRow = 320;                    // padded V row stride in LDS (bytes)
+constexpr int kKTileB = kKT * kKRow;          // 17408
+constexpr int kVTileB = kKT * kVRow;          // 20480
+constexpr int kBufB = kKTileB + kVTileB;      // one stage
+constexpr int kLdsBytes = 2 * kBufB;          // 75776: two workgroups fit in a CU's 160 KiB
 
-__device__ inline int k_swz(int row, int chunk) { return row * kRowB + ((chunk ^ (row & 15)) << 4); }
-__device__ inline int v_swz(int row, int chunk) { return row * kRowB + ((chunk ^ ((row & 3) << 2)) << 4); }
+// v_permlane32_swap exchanges the upper 32 lanes of its first operand with the lower 32 lanes
+// of its second.  Fed two copies of one value it leaves (lower half, lower half) in the first and
+// (upper half, upper half) in the second, so combining both gives every lane the reduction over
+// lane and lane^32.  Written as inline asm: the compiler builtin returns its first result twice.
+__device__ inline void half_swap(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ inline float half_swap_max(float v) {
+  float a = v, b = v;
+  half_swap(a, b);
+  return fmaxf(a, b);
+}
+__device__ inline float half_swap_sum(float v) {
+  float a = v, b = v;
+  half_swap(a, b);
+  return a + b;
+}
 
-template <int NT>
-__global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
+// NT: 32-row query tiles per wave; NW: waves per workgroup (all share the staged K/V tile).
+template <int NT, int NW>
+__global__ void __launch_bounds__(64 * NW, (NT > 1) ? 1 : 2) attn_mfma_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -53,7 +79,7 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
 
   // ---- which tile of which request, which head group (wave-uniform)
   const int HW = p.heads_per_wg;
-  const int TPW = 4 / HW;                         // token sub-tiles per workgroup
+  const int TPW = NW / HW;                        // token sub-tiles per workgroup
   const int NHG = p.n_q_heads / HW;
   int it, hg;
   {
@@ -115,45 +141,54 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
 #pragma unroll
   for (int nt = 0; nt < NT; nt++) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
 
-  // ---- global -> register -> LDS staging of one 64-key tile (4 K chunks + 4 V chunks per lane)
+  // ---- global -> register -> LDS staging of one 64-key tile.  A wave stages 4 token rows x 16
+  // chunks per pass; pass i covers tile row i*4*NW + tid/16.  The block (slot) of a pass is
+  // wave-uniform, so the load address is a scalar base plus one loop-invariant lane offset.
   const unsigned char* pool = (const unsigned char*)p.pool_layer;
   const int64_t half_b = (int64_t)kBlockTokens * Hkv * kD * 2;        // bytes of the K half of a block
-  const int ld_row = tid >> 4;      // 0..15: token row inside a block; block i of the tile = i
+  constexpr int kPass = 16 / NW;
+  const int ld_row = tid >> 4;                   // 0 .. 4*NW-1
   const int ld_chunk = tid & 15;
-  const int64_t ld_off = (int64_t)ld_row * Hkv * kD * 2 + (int64_t)kv * kD * 2 + ld_chunk * 16;
-  u32x4 kreg[4], vreg[4];
+  const unsigned ld_voff = (unsigned)((ld_row & 15) * Hkv * kD * 2 + kv * kD * 2 + ld_chunk * 16);
+  const int st_k = ld_row * kKRow + ld_chunk * 16;
+  const int st_v = kKTileB + ld_row * kVRow + ld_chunk * 16;
+  u32x4 kreg[kPass], vreg[kPass];
 
   auto load_tile = [&](int tile) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int blk = min(tile * 4 + i, last_blk);
+    for (int i = 0; i < kPass; i++) {
+      const int blk = min(tile * 4 + ((i * 4 * NW + ld_row) >> 4), last_blk);
       const int64_t slot = __builtin_amdgcn_readfirstlane(table[blk]);
-      const unsigned char* src = pool + slot * 2 * half_b + ld_off;
-      const int t = tile * kKT + i * 16 + ld_row;
-      kreg[i] = *(const u32x4*)src;
-      u32x4 v = *(const u32x4*)(src + half_b);
-      if (t >= ctx_len) v = (u32x4){0u, 0u, 0u, 0u};   // undefined tokens must not reach the PV product
-      vreg[i] = v;
+      const unsigned char* sbase = pool + slot * 2 * half_b;
+      kreg[i] = *(const u32x4*)(sbase + ld_voff);
+      vreg[i] = *(const u32x4*)(sbase + half_b + ld_voff);
+    }
+    if (tile * kKT + kKT > ctx_len) {   // tokens past the context are undefined: keep them out of PV (0 * NaN)
+#pragma unroll
+      for (int i = 0; i < kPass; i++)
+        if (tile * kKT + i * 4 * NW + ld_row >= ctx_len) vreg[i] = (u32x4){0u, 0u, 0u, 0u};
     }
   };
   auto store_tile = [&](int buf) {
-    unsigned char* kb = smem + buf * 2 * kTileB;
-    unsigned char* vb = kb + kTileB;
+    unsigned char* b = smem + buf * kBufB;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int row = i * 16 + ld_row;
-      *(u32x4*)(kb + k_swz(row, ld_chunk)) = kreg[i];
-      *(u32x4*)(vb + v_swz(row, ld_chunk)) = vreg[i];
+    for (int i = 0; i < kPass; i++) {
+      *(u32x4*)(b + st_k + i * 4 * NW * kKRow) = kreg[i];
+      *(u32x4*)(b + st_v + i * 4 * NW * kVRow) = vreg[i];
     }
   };
 
-  // lane-constant parts of the operand addresses
+  // ---- lane-constant parts of the operand addresses
+  // K operand: lane (key ln, half lh) reads 16 bytes at row ln, byte column 32*ks + 16*lh.
+  const int k_rd = ln * kKRow + lh * 16;
+  // V^T operand: 16-lane group g16 covers d = 16*(g16&1) .. +16 of a 32-wide d tile and 4 tokens
+  // starting at 4*(g16>>1); source lane s16 points at token s16/4, d offset 4*(s16%4).
   const int g16 = lane >> 4, s16 = lane & 15;
-  // V^T operand: 16-lane group g16 covers d = 16*(g16&1) .. +16 of the 32-wide d tile and the
-  // 4 tokens starting at 4*(g16>>1); source lane s16 points at token s16/4, d offset 4*(s16%4).
-  const int v_row0 = 4 * (g16 >> 1) + (s16 >> 2);
-  const int v_chunk0 = 2 * (g16 & 1) + ((s16 & 3) >> 1);
-  const int v_byte = (s16 & 1) * 8;
+  const int v_rd = kKTileB + (4 * (g16 >> 1) + (s16 >> 2)) * kVRow + (16 * (g16 & 1) + 4 * (s16 & 3)) * 2;
+
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
 
   load_tile(0);
   store_tile(0);
@@ -162,26 +197,30 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
   for (int tile = 0; tile < n_tiles; tile++) {
     const int buf = tile & 1;
     if (tile + 1 < n_tiles) load_tile(tile + 1);
-    const unsigned char* kb = smem + buf * 2 * kTileB;
-    const unsigned char* vb = kb + kTileB;
+    const unsigned char* kb = smem + buf * kBufB + k_rd;
+    const unsigned char* vb = smem + buf * kBufB + v_rd;
 
 #pragma unroll
     for (int sb = 0; sb < 2; sb++) {
       const int k0 = tile * kKT + sb * 32;
       if (wave_active && k0 <= pq_max) {
         // ---- S^T = K Q^T
+        bf16x8 ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) ka[ks] = *(const bf16x8*)(kb + sb * 32 * kKRow + ks * 32);
         f32x16 s[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++)
+        for (int nt = 0; nt < NT; nt++) {
+          f32x16 z;
 #pragma unroll
-          for (int r = 0; r < 16; r++) s[nt][r] = 0.f;
-        const int krow = sb * 32 + ln;
+          for (int r = 0; r < 16; r++) z[r] = 0.f;
+          s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[nt][0], z, 0, 0, 0);
+        }
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) {
-          const bf16x8 a = *(const bf16x8*)(kb + k_swz(krow, 2 * ks + lh));
+        for (int ks = 1; ks < 8; ks++) {
 #pragma unroll
           for (int nt = 0; nt < NT; nt++)
-            s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qB[nt][ks], s[nt], 0, 0, 0);
+            s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qB[nt][ks], s[nt], 0, 0, 0);
         }
         // ---- causal mask (only near the diagonal)
         if (k0 + 31 > pq_min) {
@@ -201,27 +240,34 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
         bool changed = false;
 #pragma unroll
         for (int nt = 0; nt < NT; nt++) {
-          float mx = s[nt][0];
+          float mx = fmaxf(s[nt][0], s[nt][1]);
 #pragma unroll
-          for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[nt][r]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[nt][r]), s[nt][r + 1]);
+          mx = half_swap_max(mx);
           const float m_new = fmaxf(m_run[nt], mx);
           alpha[nt] = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * c2);
           changed |= (m_new != m_run[nt]);
           m_run[nt] = m_new;
           const float mc = m_new * c2;
+          // weights are rounded to bf16 once; the row sum adds the rounded values (v_dot2 against
+          // (1,1)), so numerator and denominator of the softmax use the same numbers
           float ps = 0.f;
-          float pv[16];
+          bf16x2 pk[8];
 #pragma unroll
-          for (int r = 0; r < 16; r++) {
-            pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][r], c2, -mc));
-            ps += pv[r];
+          for (int e = 0; e < 8; e++) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][2 * e], c2, -mc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][2 * e + 1], c2, -mc));
+            pk[e][0] = (__bf16)p0;
+            pk[e][1] = (__bf16)p1;
+            ps = __builtin_amdgcn_fdot2_f32_bf16(pk[e], ones, ps, false);
           }
           l_run[nt] = l_run[nt] * alpha[nt] + ps;
 #pragma unroll
-          for (int j = 0; j < 2; j++)
-#pragma unroll
-            for (int e = 0; e < 8; e++) pb[nt][j][e] = (__bf16)pv[8 * j + e];
+          for (int j = 0; j < 2; j++) {
+            u32x4 w = {__builtin_bit_cast(unsigned, pk[4 * j]), __builtin_bit_cast(unsigned, pk[4 * j + 1]),
+                       __builtin_bit_cast(unsigned, pk[4 * j + 2]), __builtin_bit_cast(unsigned, pk[4 * j + 3])};
+            pb[nt][j] = __builtin_bit_cast(bf16x8, w);
+          }
         }
         if (__builtin_amdgcn_ballot_w64(changed) != 0) {
 #pragma unroll
@@ -236,12 +282,10 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
         for (int j = 0; j < 2; j++) {
 #pragma unroll
           for (int dt = 0; dt < 4; dt++) {
-            const int row_a = sb * 32 + 16 * j + v_row0;
-            const int chunk = 4 * dt + v_chunk0;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3)))*)(vb + v_swz(row_a, chunk) + v_byte));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3)))*)(vb + v_swz(row_a + 8, chunk) + v_byte));
+            const unsigned char* va = vb + (sb * 32 + 16 * j) * kVRow + dt * 64;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va));
+            const s16x4 hi =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(va + 8 * kVRow));
             const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 a = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
@@ -261,7 +305,7 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
     unsigned short* out = (unsigned short*)p.out;
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) {
-      const float lt = l_run[nt] + __shfl_xor(l_run[nt], 32);
+      const float lt = half_swap_sum(l_run[nt]);
       const float inv = 1.f / lt;
       const int tokq = wq0 + nt * 32 + ln;
       if (tokq < S) {
@@ -283,22 +327,42 @@ __global__ void __launch_bounds__(256, 1) attn_mfma_kernel(AttnParams p) {
   }
 }
 
-constexpr int kNT = 2;
+// Kernel shape.  Variant 0 (default): 4 waves x 32 rows, two workgroups per CU.  Variant 1:
+// 4 waves x 64 rows (half the LDS operand traffic, one wave per SIMD).  Variant 2: 8 waves x
+// 32 rows in one workgroup.  CALVO_ATTN_VARIANT selects a shape for tuning runs.
+static int attn_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("CALVO_ATTN_VARIANT");
+    v = (e && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0;
+  }
+  return v;
+}
 
-int attn_mfma_tile_tokens(int heads_per_wg) { return 32 * kNT * (4 / heads_per_wg); }
+int attn_mfma_tile_tokens(int heads_per_wg) {
+  const int v = attn_variant();
+  return v == 1 ? 64 * (4 / heads_per_wg) : v == 2 ? 32 * (8 / heads_per_wg) : 32 * (4 / heads_per_wg);
+}
 
-hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
-  if (p.n_items <= 0) return hipSuccess;
+template <int NT, int NW>
+static hipError_t launch_variant(const AttnParams& p, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<kNT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kLdsBytes);
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<NT, NW>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const unsigned grid = (unsigned)p.n_items * (unsigned)(p.n_q_heads / p.heads_per_wg);
-  hipLaunchKernelGGL(attn_mfma_kernel<kNT>, dim3(grid), dim3(256), kLdsBytes, stream, p);
+  hipLaunchKernelGGL((attn_mfma_kernel<NT, NW>), dim3(grid), dim3(64 * NW), kLdsBytes, stream, p);
   return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
+  if (p.n_items <= 0) return hipSuccess;
+  const int v = attn_variant();
+  return v == 1 ? launch_variant<2, 4>(p, stream) : v == 2 ? launch_variant<1, 8>(p, stream)
+                                                          : launch_variant<1, 4>(p, stream);
 }
 
 }  // namespace calvo

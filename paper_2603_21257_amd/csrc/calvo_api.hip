@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -212,6 +213,10 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->n_staging = cfg->staging_bytes ? (cfg->n_staging ? cfg->n_staging : 2) : 0;
   c->n_copy = cfg->n_copy_streams ? cfg->n_copy_streams : 1;
   c->staging_blocks = cfg->staging_bytes / c->blk_bytes;
+  if (const char* e = getenv("CALVO_SCATTER_GRID")) {   // tuning knob: workgroups of the zero-copy scatter
+    const int g = atoi(e);
+    if (g >= 1 && g <= 4096) c->scatter_grid = g;
+  }
 
 #define CREATE_TRY(expr)                                                        \
   do {                                                                          \
