@@ -8,10 +8,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcalvo.so")
-SOURCES = ["calvo_api.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_mfma.hip"]
+SOURCES = ["calvo_api.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_mfma.hip", "attn_pipe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-result", "-fgpu-rdc" if False else "-fno-gpu-rdc"]
+         "-Wno-unused-result", "-fno-gpu-rdc"]
 
 
 def build(verbose: bool = False) -> str:

@@ -334,13 +334,14 @@ static int attn_variant() {
   static int v = -1;
   if (v < 0) {
     const char* e = getenv("CALVO_ATTN_VARIANT");
-    v = (e && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0;
+    v = (e && e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 0;
   }
   return v;
 }
 
 int attn_mfma_tile_tokens(int heads_per_wg) {
   const int v = attn_variant();
+  if (v == 3) return attn_pipe_tile_tokens(heads_per_wg);
   return v == 1 ? 64 * (4 / heads_per_wg) : v == 2 ? 32 * (8 / heads_per_wg) : 32 * (4 / heads_per_wg);
 }
 
@@ -361,6 +362,7 @@ static hipError_t launch_variant(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
   const int v = attn_variant();
+  if (v == 3) return launch_attn_pipe(p, stream);
   return v == 1 ? launch_variant<2, 4>(p, stream) : v == 2 ? launch_variant<1, 8>(p, stream)
                                                           : launch_variant<1, 4>(p, stream);
 }

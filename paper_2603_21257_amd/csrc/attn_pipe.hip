@@ -1,0 +1,456 @@
+// Paged causal GQA prefill attention for gfx950 (CDNA4), software-pipelined kernel:
+// bf16 storage, head_dim 128, v_mfma_f32_32x32x16_bf16 for both contractions, fp32 online
+// softmax.  Transposed formulation as in attn_mfma.hip (S^T = K Q^T, O^T += V^T P^T, all
+// softmax statistics lane-local, V^T fetched with the LDS transpose read ds_read_b64_tr_b16).
+//
+// Schedule.  The key loop advances in 32-key sub-tiles.  For sub-tile j the stages
+//     QK(j):  S_j = K_j Q^T                                     8 MFMA
+//     SM(j):  m, alpha, P_j = exp2(c (S_j - m)), row sums       ~60 vector-ALU instructions
+//     PV(j):  O^T = alpha O^T + V_j^T P_j^T                     8 MFMA
+// depend on each other, but QK(t+1), SM(t) and PV(t-1) do not.  Step t issues exactly these
+// three, interleaved in 16 slots of one MFMA plus a share of the exponentials, so the matrix
+// pipe always has an independent MFMA to run while the vector ALU works through the softmax.
+// S and P are double buffered in registers; the steady loop is unrolled by four so that
+// register buffers and LDS ring slots are named statically.
+//
+// Data movement.  K and V go from the pool straight into LDS with global_load_lds_dwordx4
+// (no register staging): each wave instruction deposits 4 token rows x 256 B.  Two rings of
+// four 8 KiB slots (K and V separately, because K_j is consumed two steps before V_j):
+// at step t the workgroup requests K(t+4) and V(t+2), reads K(t+1) and V(t-1), and ends with
+// s_waitcnt vmcnt(8) + one barrier, which guarantees K(t+2) and V(t) - requested two steps
+// earlier - have landed.  Rows are unpadded; 16-byte chunks are XOR-swizzled on the way in
+// (the lane that owns LDS chunk position c fetches logical chunk c ^ f(row)) so that operand
+// reads are bank-conflict free: K f = row & 15, V f = (row & 3) << 2.  All operand addresses
+// are lane constants (8 for K, 4 for V) plus compile-time offsets.
+//
+// Sub-tiles that touch the causal diagonal or the end of the context are not pipelined: they
+// are at most a handful per workgroup and are loaded synchronously and run QK -> mask -> SM ->
+// PV one after the other.
+#include "calvo_internal.h"
+
+namespace calvo {
+namespace pipe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+
+constexpr int kD = 128;
+constexpr int kSK = 32;                        // keys per sub-tile / ring slot
+constexpr int kRow = 256;                      // bytes per token row of one head
+constexpr int kSlot = kSK * kRow;              // 8192
+constexpr int kRing = 4;
+constexpr int kVBase = kRing * kSlot;          // V ring follows the K ring
+constexpr int kLdsBytes = 2 * kRing * kSlot;   // 65536: two workgroups per CU
+
+template <int V>
+struct Tag { static constexpr int value = V; };
+
+// lanes [32,64) of a <-> lanes [0,32) of b (the compiler builtin for this instruction returns
+// its first result twice, hence inline asm)
+__device__ inline void half_swap(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ inline float half_swap_max(float v) {
+  float a = v, b = v;
+  half_swap(a, b);
+  return fmaxf(a, b);
+}
+__device__ inline float half_swap_sum(float v) {
+  float a = v, b = v;
+  half_swap(a, b);
+  return a + b;
+}
+
+// 64 lanes x 16 bytes from global memory (uniform base + per-lane byte offset) to 1 KiB of LDS
+// starting at lds_addr (uniform).  Completion is tracked by vmcnt.  No "memory" clobber on
+// purpose: every read of the deposited data sits behind wait_vm + a workgroup barrier, and a
+// clobber would stop the compiler from keeping the block-table loads on the scalar unit.
+__device__ inline void dma_1k(const unsigned char* sbase, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_addr));
+}
+template <int N>
+__device__ inline void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
+}
+
+__device__ inline bf16x8 read_k(const lds_u8* a) { return *(const __attribute__((address_space(3))) bf16x8*)a; }
+__device__ inline bf16x8 read_vt(const lds_u8* a) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a + 8 * kRow));
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+__global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int NW = 4;
+  const lds_u8* lds = (const lds_u8*)smem;
+  const unsigned lds0 = (unsigned)(size_t)lds;   // LDS byte address of the ring
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31;
+  const int lh = lane >> 5;
+
+  // ---- work item decode (wave-uniform)
+  const int HW = p.heads_per_wg;
+  const int TPW = NW / HW;
+  const int NHG = p.n_q_heads / HW;
+  int it, hg;
+  {
+    const int bid = blockIdx.x;
+    if ((NHG & 7) == 0) {                         // keep one KV head's workgroups on one XCD
+      const int per = NHG >> 3, rest = bid >> 3;
+      hg = (bid & 7) * per + rest % per;
+      it = rest / per;
+    } else {
+      hg = bid % NHG;
+      it = bid / NHG;
+    }
+  }
+  const WorkItem wi = p.items[it];
+  const ReqDesc rd = p.reqs[wi.req];
+  const int P = rd.prefix_len, S = rd.suffix_len;
+  const int TQ = 32 * TPW;
+  const int q_base = wi.q_tile * TQ;
+  const int hq = hg * HW + wave % HW;
+  const int kv = hq / (p.n_q_heads / p.n_kv_heads);
+  const int wq0 = q_base + (wave / HW) * 32;
+  const bool wave_active = wq0 < S;
+  const int pq_min = P + wq0;
+  const int pq_max = P + min(wq0 + 32, S) - 1;
+  const int ctx_len = P + S;
+  const int n_keys = P + min(q_base + TQ, S);
+  const int n_sub = (n_keys + kSK - 1) / kSK;                 // sub-tiles this workgroup visits
+  const int n_pipe = min(n_sub, (P + q_base + 1) / kSK);      // ... fully visible to all its rows
+  const int last_blk = (ctx_len + kBlockTokens - 1) / kBlockTokens - 1;
+  // the block table is read-only for the whole launch: reading it through the constant address
+  // space keeps the lookups on the scalar unit, outside the vmcnt accounting of the K/V requests
+  typedef const __attribute__((address_space(4))) int32_t* const_i32p;
+  const const_i32p table = (const_i32p)(uintptr_t)(p.tables + rd.table_off);
+  typedef const __attribute__((address_space(4))) int64_t* const_i64p;
+  const const_i64p boffs = (const_i64p)(uintptr_t)(p.blk_offs + rd.table_off);   // slot * block bytes, padded
+  const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
+  const float c2 = p.scale * 1.4426950408889634f;
+
+  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8]
+  bf16x8 qB[8];
+  {
+    const unsigned short* q = (const unsigned short*)p.q;
+    const int tokq = wq0 + ln;
+    const bool ok = tokq < S;
+    const unsigned short* row = q + ((int64_t)(rd.q_off + (ok ? tokq : 0)) * Hq + hq) * kD + 8 * lh;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (ok) v = *(const u32x4*)(row + 16 * ks);
+      qB[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  f32x16 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches rows 4w..4w+3 of each
+  // block (one instruction per block for K and one for V); lane l owns row 4w + l/16 and LDS
+  // chunk position l%16, and fetches the logical chunk that the swizzle maps there.
+  const unsigned char* pool = (const unsigned char*)p.pool_layer;
+  const int64_t half_b = (int64_t)kBlockTokens * Hkv * kD * 2;         // K half of a block, bytes
+  const int brow = 4 * wave + (lane >> 4);                             // row inside the block
+  const unsigned rowoff = (unsigned)(brow * Hkv * kD * 2 + kv * kD * 2);
+  const unsigned voff_k = rowoff + (((lane & 15) ^ (brow & 15)) << 4);
+  const unsigned voff_v = rowoff + (((lane & 15) ^ ((brow & 3) << 2)) << 4);
+  const unsigned dma_lds = lds0 + wave * 1024;                         // + slot*8192 + block*4096 (+ V ring)
+
+  // byte offsets of the two blocks of sub-tile j (the table is padded, so j may run past the end)
+  struct Pair { int64_t b0, b1; };
+  auto fetch_pair = [&](int j) -> Pair { return Pair{boffs[2 * j], boffs[2 * j + 1]}; };
+  auto request_k_at = [&](const Pair& pr, int slot) {
+    dma_1k(pool + pr.b0, voff_k, dma_lds + slot * kSlot);
+    dma_1k(pool + pr.b1, voff_k, dma_lds + slot * kSlot + 4096);
+  };
+  auto request_v_at = [&](const Pair& pr, int slot) {
+    dma_1k(pool + half_b + pr.b0, voff_v, dma_lds + kVBase + slot * kSlot);
+    dma_1k(pool + half_b + pr.b1, voff_v, dma_lds + kVBase + slot * kSlot + 4096);
+  };
+  auto request_k = [&](int j) { request_k_at(fetch_pair(j), j & (kRing - 1)); };
+  auto request_v = [&](int j) { request_v_at(fetch_pair(j), j & (kRing - 1)); };
+  // synchronous variant for the sub-tiles at the end: rows past the context are not fetched,
+  // their V is written as zeros so that undefined pool bytes cannot reach the PV product
+  auto request_tail = [&](int j) {
+#pragma unroll
+    for (int b = 0; b < 2; b++) {
+      const int64_t boff = boffs[2 * j + b];
+      const bool live = j * kSK + b * 16 + brow < ctx_len;
+      const unsigned l_k = dma_lds + (j & (kRing - 1)) * kSlot + b * 4096;
+      if (live) {
+        dma_1k(pool + boff, voff_k, l_k);
+        dma_1k(pool + boff + half_b, voff_v, l_k + kVBase);
+      } else {
+        *(u32x4*)(smem + (l_k - lds0) + kVBase + (lane << 4)) = (u32x4){0u, 0u, 0u, 0u};
+      }
+    }
+  };
+
+  // ---- lane-constant operand addresses inside a slot
+  // K operand: row ln, logical chunk 2ks+lh
+  const lds_u8* ka_addr[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) ka_addr[ks] = lds + ln * kRow + (((2 * ks + lh) ^ (ln & 15)) << 4);
+  // V^T operand: 16-lane group g16 covers d = 16*(g16&1)..+16 of a 32-wide d tile and 4 tokens
+  // starting at 4*(g16>>1); source lane s16 points at token s16/4, d offset 4*(s16%4)
+  const int g16 = lane >> 4, s16 = lane & 15;
+  const int v_row = 4 * (g16 >> 1) + (s16 >> 2);
+  const int v_c0 = 2 * (g16 & 1) + ((s16 & 3) >> 1);
+  const lds_u8* va_addr[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+    va_addr[dt] = lds + kVBase + v_row * kRow + ((4 * (dt ^ (v_row & 3)) + v_c0) << 4) + (s16 & 1) * 8;
+
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
+
+  // ---- pipeline registers: S and P of two consecutive sub-tiles
+  f32x16 sbuf[2];
+  bf16x8 pbuf[2][2];
+  float al[2] = {1.f, 1.f};
+  bool chg[2] = {false, false};
+
+  auto rescale = [&](float a) {
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) o[dt][r] *= a;
+  };
+  auto qk = [&](int slot, f32x16& s) {
+    bf16x8 ka[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) ka[ks] = read_k(ka_addr[ks] + slot * kSlot);
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; r++) z[r] = 0.f;
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
+#pragma unroll
+    for (int ks = 1; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qB[ks], s, 0, 0, 0);
+  };
+  // statistics of one sub-tile: new running max, rescale factor, scaled max
+  auto sm_head = [&](const f32x16& s, float& alpha, bool& changed, float& mc) {
+    float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+    mx = half_swap_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    changed = (m_new != m_run);
+    m_run = m_new;
+    mc = m_new * c2;
+  };
+  // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the rounded
+  // values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
+  auto sm_pair = [&](const f32x16& s, int e, float mc, float& ps) -> unsigned {
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, -mc));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, -mc));
+    bf16x2 pk;
+    pk[0] = (__bf16)p0;
+    pk[1] = (__bf16)p1;
+    ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
+    return __builtin_bit_cast(unsigned, pk);
+  };
+  auto sm_all = [&](const f32x16& s, bf16x8 (&pb)[2], float& alpha, bool& changed) {
+    float mc, ps = 0.f;
+    sm_head(s, alpha, changed, mc);
+    unsigned pk[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) pk[e] = sm_pair(s, e, mc, ps);
+    l_run = l_run * alpha + ps;
+    pb[0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+    pb[1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+  };
+  auto pv = [&](int slot, const bf16x8 (&pb)[2]) {
+#pragma unroll
+    for (int jj = 0; jj < 2; jj++)
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        const bf16x8 a = read_vt(va_addr[dt] + slot * kSlot + 16 * jj * kRow);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[jj], o[dt], 0, 0, 0);
+      }
+  };
+
+  // ---- steady step t (t & 3 == T4): QK(t+1), SM(t), PV(t-1) interleaved.
+  Pair ring[4];                                    // block offsets of sub-tiles in flight
+  auto step_steady = [&](auto t4, int t) {
+    constexpr int T4 = decltype(t4)::value;
+    constexpr int C = T4 & 1, N = C ^ 1;             // S/P of sub-tile t live in buffer C
+    constexpr int KS = (T4 + 1) & 3, VS = (T4 + 3) & 3;   // ring slots of K(t+1), V(t-1)
+    if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
+    request_k_at(ring[T4], T4);                      // K(t+4)
+    request_v_at(ring[(T4 + 2) & 3], (T4 + 2) & 3);  // V(t+2)
+    ring[(T4 + 1) & 3] = fetch_pair(t + 5);          // for the next step
+    bf16x8 ka[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) ka[k] = read_k(ka_addr[k] + KS * kSlot);
+    float alpha, mc, ps = 0.f;
+    bool changed;
+    sm_head(sbuf[C], alpha, changed, mc);
+    unsigned pk[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) pk[e] = sm_pair(sbuf[C], e, mc, ps);
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; r++) z[r] = 0.f;
+    f32x16 sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
+#pragma unroll
+    for (int k = 1; k < 8; k++) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+      const bf16x8 va = read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
+      o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
+    }
+    sbuf[N] = sn;
+    l_run = l_run * alpha + ps;
+    pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+    pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+    al[C] = alpha;
+    chg[C] = changed;
+    // Order for the machine scheduler: the wave alternates between a vector-ALU phase (softmax of
+    // sub-tile t, with the K operands of QK(t+1) already on their way from LDS) and an MFMA phase
+    // (QK(t+1) while the V operands arrive, then PV(t-1)); the second wave of the SIMD runs the
+    // opposite phase.
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: K operands
+    __builtin_amdgcn_sched_group_barrier(0x402, 96, 0);   // VALU + TRANS: the whole softmax
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: first four V operands
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);    // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: last four V operands
+    __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);   // MFMA
+    wait_vm<8>();          // everything but the 8 requests of this and the previous step has landed
+    __syncthreads();
+  };
+
+  // fill and drain of the pipeline: same three parts, each guarded, one after the other
+  auto step_edge = [&](auto par, int t) {
+    constexpr int C = decltype(par)::value, N = C ^ 1;
+    request_k(t + 4);
+    request_v(t + 2);
+    if (t + 1 < n_pipe) qk((t + 1) & 3, sbuf[N]);
+    if (t >= 1 && t <= n_pipe) {
+      if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
+      pv((t - 1) & 3, pbuf[N]);
+    }
+    if (t < n_pipe) sm_all(sbuf[C], pbuf[C], al[C], chg[C]);
+    wait_vm<0>();
+    __syncthreads();
+  };
+
+  // ---- prologue: K(0..3), V(0..1) resident, S_0 computed
+#pragma unroll
+  for (int j = 0; j < 4; j++) request_k(j);
+  request_v(0);
+  request_v(1);
+  wait_vm<0>();
+  __syncthreads();
+  if (n_pipe > 0) qk(0, sbuf[0]);
+
+  int t = 0;
+  step_edge(Tag<0>{}, t++);                                   // t = 0: QK(1), SM(0)
+  if (t + 4 < n_pipe) {
+    // steady steps need 1 <= t and t + 1 < n_pipe; the unrolled loop is entered at t = 1 with the
+    // block offsets of sub-tiles t+2, t+3, t+4 in their ring entries
+    ring[3] = fetch_pair(t + 2);
+    ring[0] = fetch_pair(t + 3);
+    ring[1] = fetch_pair(t + 4);
+    ring[2] = ring[1];
+    for (; t + 4 < n_pipe; t += 4) {
+      step_steady(Tag<1>{}, t);
+      step_steady(Tag<2>{}, t + 1);
+      step_steady(Tag<3>{}, t + 2);
+      step_steady(Tag<0>{}, t + 3);
+    }
+  }
+  for (; t <= n_pipe; t++) {                                  // remaining pipelined steps and drain
+    if (t & 1) step_edge(Tag<1>{}, t);
+    else step_edge(Tag<0>{}, t);
+  }
+
+  // ---- sub-tiles on or past the diagonal: synchronous load, plain path
+  for (int j = n_pipe; j < n_sub; j++) {
+    request_tail(j);
+    wait_vm<0>();
+    __syncthreads();
+    const int k0 = j * kSK;
+    if (wave_active && k0 <= pq_max) {
+      f32x16 s;
+      qk(j & 3, s);
+      if (k0 + 31 > pq_min) {
+        const int pq = pq_min + ln;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int kt = k0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (kt > pq) s[r] = -INFINITY;
+        }
+      }
+      bf16x8 pb[2];
+      float alpha;
+      bool changed;
+      sm_all(s, pb, alpha, changed);
+      if (__builtin_amdgcn_ballot_w64(changed) != 0) rescale(alpha);
+      pv(j & 3, pb);
+    }
+    __syncthreads();
+  }
+
+  // ---- normalise and write O[token][head][d]; lane holds d = 32dt + 8(r/4) + 4lh + r%4
+  if (wave_active) {
+    unsigned short* out = (unsigned short*)p.out;
+    const float lt = half_swap_sum(l_run);
+    const float inv = 1.f / lt;
+    const int tokq = wq0 + ln;
+    if (tokq < S) {
+      unsigned short* row = out + ((int64_t)(rd.q_off + tokq) * Hq + hq) * kD + 4 * lh;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int rq = 0; rq < 4; rq++) {
+          bf16x2 a, b;
+          a[0] = (__bf16)(o[dt][4 * rq + 0] * inv);
+          a[1] = (__bf16)(o[dt][4 * rq + 1] * inv);
+          b[0] = (__bf16)(o[dt][4 * rq + 2] * inv);
+          b[1] = (__bf16)(o[dt][4 * rq + 3] * inv);
+          u32x2 w = {__builtin_bit_cast(unsigned int, a), __builtin_bit_cast(unsigned int, b)};
+          *(u32x2*)(row + 32 * dt + 8 * rq) = w;
+        }
+    }
+  }
+}
+
+}  // namespace pipe
+
+int attn_pipe_tile_tokens(int heads_per_wg) { return 32 * (4 / heads_per_wg); }
+
+hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream) {
+  if (p.n_items <= 0) return hipSuccess;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)pipe::attn_pipe_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, pipe::kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const unsigned grid = (unsigned)p.n_items * (unsigned)(p.n_q_heads / p.heads_per_wg);
+  hipLaunchKernelGGL(pipe::attn_pipe_kernel, dim3(grid), dim3(256), pipe::kLdsBytes, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace calvo

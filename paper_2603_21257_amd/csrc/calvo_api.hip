@@ -407,7 +407,11 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const int HW = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
   const int tile_tokens = mfma ? attn_mfma_tile_tokens(HW) : 1;
 
-  // ---- descriptor blob: requests, work items (heaviest first), tables
+  // ---- descriptor blob: requests, work items (heaviest first), block tables, block byte offsets.
+  // Each request's table is followed by kTablePad copies of its last entry so that a kernel may
+  // look a few blocks past the end without clamping; blk_offs holds slot * block_bytes (the byte
+  // offset of the block inside a layer of the pool) for the same indices.
+  constexpr int kTablePad = 16;
   std::vector<int32_t> blob;
   blob.reserve(4 * n_reqs + 1024);
   size_t n_tab = 0;
@@ -417,7 +421,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     blob.push_back(reqs[r].n_prefix_blocks * kBlockTokens);
     blob.push_back(reqs[r].suffix_len);
     blob.push_back(cu_suffix[r]);
-    n_tab += (size_t)nt;
+    n_tab += (size_t)nt + kTablePad;
   }
   struct Item { int32_t req, tile; int64_t cost; };
   std::vector<Item> items;
@@ -436,6 +440,14 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   for (int r = 0; r < n_reqs; r++) {
     const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
     blob.insert(blob.end(), reqs[r].block_table, reqs[r].block_table + nt);
+    blob.insert(blob.end(), kTablePad, nt > 0 ? reqs[r].block_table[nt - 1] : 0);
+  }
+  if (blob.size() & 1) blob.push_back(0);                       // 8-byte alignment of the offsets
+  const size_t offs_off = blob.size();
+  for (size_t i = 0; i < n_tab; i++) {
+    const int64_t off = (int64_t)blob[tables_off + i] * (int64_t)c->blk_bytes;
+    blob.push_back((int32_t)(uint32_t)(off & 0xffffffff));
+    blob.push_back((int32_t)(off >> 32));
   }
 
   rc = ensure_att_blob(c, blob.size());
@@ -467,6 +479,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   AttnParams p{};
   p.q = q; p.out = out; p.pool_layer = pool_layer;
   p.reqs = d_reqs; p.items = (const WorkItem*)(c->d_att + items_off); p.tables = d_tables;
+  p.blk_offs = (const int64_t*)(c->d_att + offs_off);
   p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
   p.heads_per_wg = HW; p.tile_tokens = tile_tokens;
   p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);

@@ -26,7 +26,8 @@ struct AttnParams {
   const void* pool_layer;   // this layer's [pool_blocks][2][B][Hkv][D]
   const ReqDesc* reqs;
   const WorkItem* items;
-  const int32_t* tables;
+  const int32_t* tables;    // per request: its block table, then 16 copies of the last entry
+  const int64_t* blk_offs;  // same indexing: slot * block_bytes
   int32_t n_items;          // tiles over all requests
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
@@ -52,6 +53,8 @@ hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
 int attn_mfma_tile_tokens(int heads_per_wg);
+hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
+int attn_pipe_tile_tokens(int heads_per_wg);
 
 constexpr int kBlockTokens = 16;
 
