@@ -327,14 +327,15 @@ __global__ void __launch_bounds__(64 * NW, (NT > 1) ? 1 : 2) attn_mfma_kernel(At
   }
 }
 
-// Kernel shape.  Variant 0 (default): 4 waves x 32 rows, two workgroups per CU.  Variant 1:
-// 4 waves x 64 rows (half the LDS operand traffic, one wave per SIMD).  Variant 2: 8 waves x
-// 32 rows in one workgroup.  CALVO_ATTN_VARIANT selects a shape for tuning runs.
+// Kernel choice.  Variant 3 (default): the software-pipelined kernel of attn_pipe.hip.  The
+// unpipelined kernel of this file stays available for comparison runs through the environment
+// variable CALVO_ATTN_VARIANT: 0 = 4 waves x 32 rows, two workgroups per CU; 1 = 4 waves x 64
+// rows (half the LDS operand traffic, one wave per SIMD); 2 = 8 waves x 32 rows.
 static int attn_variant() {
   static int v = -1;
   if (v < 0) {
     const char* e = getenv("CALVO_ATTN_VARIANT");
-    v = (e && e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 0;
+    v = (e && e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 3;
   }
   return v;
 }

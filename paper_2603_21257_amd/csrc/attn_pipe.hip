@@ -10,18 +10,25 @@
 // depend on each other, but QK(t+1), SM(t) and PV(t-1) do not.  Step t issues exactly these
 // three, interleaved in 16 slots of one MFMA plus a share of the exponentials, so the matrix
 // pipe always has an independent MFMA to run while the vector ALU works through the softmax.
-// S and P are double buffered in registers; the steady loop is unrolled by four so that
-// register buffers and LDS ring slots are named statically.
+// S and P are double buffered in registers; the steady loop is unrolled by eight so that
+// register buffers and LDS ring slots are named statically (eight-fold for the ring).
 //
 // Data movement.  K and V go from the pool straight into LDS with global_load_lds_dwordx4
 // (no register staging): each wave instruction deposits 4 token rows x 256 B.  Two rings of
-// four 8 KiB slots (K and V separately, because K_j is consumed two steps before V_j):
-// at step t the workgroup requests K(t+4) and V(t+2), reads K(t+1) and V(t-1), and ends with
-// s_waitcnt vmcnt(8) + one barrier, which guarantees K(t+2) and V(t) - requested two steps
-// earlier - have landed.  Rows are unpadded; 16-byte chunks are XOR-swizzled on the way in
-// (the lane that owns LDS chunk position c fetches logical chunk c ^ f(row)) so that operand
-// reads are bank-conflict free: K f = row & 15, V f = (row & 3) << 2.  All operand addresses
-// are lane constants (8 for K, 4 for V) plus compile-time offsets.
+// eight 8 KiB slots (K and V separately, because K_j is consumed two steps before V_j): at
+// step t the workgroup requests K(t+8) and V(t+6), reads K(t+1) and V(t-1), and ends with
+// s_waitcnt vmcnt(12) + one barrier, which guarantees K(t+2) and V(t) - requested six steps
+// earlier - have landed.  The deep ring matters: all workgroups of an XCD walk the same K/V
+// stream, whoever is first pays the full HBM latency, and only requests issued several steps
+// ahead keep that latency off the critical path.  Rows are unpadded; 16-byte chunks are
+// XOR-swizzled on the way in (the lane that owns LDS chunk position c fetches logical chunk
+// c ^ f(row)) so that operand reads are bank-conflict free: K f = row & 15, V f = (row & 3) << 2.
+// All operand addresses are lane constants (8 for K, 4 for V) plus compile-time offsets.
+//
+// Workgroup = 8 waves = 4 query heads of one KV group x 2 token tiles of 32; waves w and w+4
+// share a SIMD.  Within a step waves 0-3 run softmax first and MFMAs second, waves 4-7 the
+// other way round, so each SIMD always has one wave feeding the matrix pipe while the other
+// uses the vector ALU.
 //
 // Sub-tiles that touch the causal diagonal or the end of the context are not pipelined: they
 // are at most a handful per workgroup and are loaded synchronously and run QK -> mask -> SM ->
@@ -44,9 +51,13 @@ constexpr int kD = 128;
 constexpr int kSK = 32;                        // keys per sub-tile / ring slot
 constexpr int kRow = 256;                      // bytes per token row of one head
 constexpr int kSlot = kSK * kRow;              // 8192
-constexpr int kRing = 4;
+constexpr int kRing = 8;
 constexpr int kVBase = kRing * kSlot;          // V ring follows the K ring
-constexpr int kLdsBytes = 2 * kRing * kSlot;   // 65536: two workgroups per CU
+// furthest sub-tile whose block offsets are fetched: n_pipe + 2 * kRing - 2, with n_pipe at most
+// half the number of real blocks (rounded up); each parity half of the padded table holds
+// (real blocks + kTablePad) / 2 entries
+static_assert(kTablePad >= 4 * kRing, "block table padding too small for the ring depth");
+constexpr int kLdsBytes = 2 * kRing * kSlot;   // 131072: one 8-wave workgroup per CU
 
 template <int V>
 struct Tag { static constexpr int value = V; };
@@ -76,6 +87,12 @@ __device__ inline void dma_1k(const unsigned char* sbase, unsigned voff, unsigne
                :
                : "v"(voff), "s"(sbase), "s"(lds_addr));
 }
+// compiler-level fence for one value: it is 'rewritten' here, so its producers stay above this
+// point and its consumers below it; emits no instruction
+template <typename T>
+__device__ inline void pin(T& x) {
+  asm volatile("" : "+v"(x));
+}
 template <int N>
 __device__ inline void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
@@ -89,9 +106,13 @@ __device__ inline bf16x8 read_vt(const lds_u8* a) {
   return __builtin_bit_cast(bf16x8, both);
 }
 
-__global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
+// 240 of the 256 registers a wave may have at two waves per SIMD (the attribute counts half of
+// the unified VGPR+AGPR file on this target): the remaining 32 per SIMD lane
+// let a wave of the ingest scatter kernel become resident next to the attention waves, so the
+// loading stage keeps moving while attention occupies every CU.
+__global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) attn_pipe_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int NW = 4;
+  constexpr int NW = 8;
   const lds_u8* lds = (const lds_u8*)smem;
   const unsigned lds0 = (unsigned)(size_t)lds;   // LDS byte address of the ring
   const int tid = threadIdx.x;
@@ -137,7 +158,9 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
   typedef const __attribute__((address_space(4))) int32_t* const_i32p;
   const const_i32p table = (const_i32p)(uintptr_t)(p.tables + rd.table_off);
   typedef const __attribute__((address_space(4))) int64_t* const_i64p;
-  const const_i64p boffs = (const_i64p)(uintptr_t)(p.blk_offs + rd.table_off);   // slot * block bytes, padded
+  const int n_blk_pad = last_blk + 1 + kTablePad + ((last_blk + 1) & 1);            // entries of the padded table
+  // this wave's half of every sub-tile: block 2j + (wave >> 2); offsets of one parity are contiguous
+  const const_i64p boffs = (const_i64p)(uintptr_t)(p.blk_offs + rd.table_off + (wave >> 2) * (n_blk_pad >> 1));
   const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
   const float c2 = p.scale * 1.4426950408889634f;
 
@@ -163,44 +186,37 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
     for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches rows 4w..4w+3 of each
-  // block (one instruction per block for K and one for V); lane l owns row 4w + l/16 and LDS
-  // chunk position l%16, and fetches the logical chunk that the swizzle maps there.
+  // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches rows 4(w&3)..+3 of block
+  // 2j + (w>>2): one instruction for K and one for V per sub-tile.  Lane l owns row 4(w&3) + l/16
+  // and LDS chunk position l%16, and fetches the logical chunk that the swizzle maps there.
   const unsigned char* pool = (const unsigned char*)p.pool_layer;
   const int64_t half_b = (int64_t)kBlockTokens * Hkv * kD * 2;         // K half of a block, bytes
-  const int brow = 4 * wave + (lane >> 4);                             // row inside the block
+  const int wblk = wave >> 2;                                          // which block of the sub-tile
+  const int brow = 4 * (wave & 3) + (lane >> 4);                       // row inside the block
   const unsigned rowoff = (unsigned)(brow * Hkv * kD * 2 + kv * kD * 2);
   const unsigned voff_k = rowoff + (((lane & 15) ^ (brow & 15)) << 4);
   const unsigned voff_v = rowoff + (((lane & 15) ^ ((brow & 3) << 2)) << 4);
-  const unsigned dma_lds = lds0 + wave * 1024;                         // + slot*8192 + block*4096 (+ V ring)
+  const unsigned dma_lds = lds0 + wave * 1024;                         // + slot*8192 (+ V ring)
 
-  // byte offsets of the two blocks of sub-tile j (the table is padded, so j may run past the end)
-  struct Pair { int64_t b0, b1; };
-  auto fetch_pair = [&](int j) -> Pair { return Pair{boffs[2 * j], boffs[2 * j + 1]}; };
-  auto request_k_at = [&](const Pair& pr, int slot) {
-    dma_1k(pool + pr.b0, voff_k, dma_lds + slot * kSlot);
-    dma_1k(pool + pr.b1, voff_k, dma_lds + slot * kSlot + 4096);
+  // byte offset of this wave's block of sub-tile j (the table is padded, so j may run past the end)
+  auto fetch_off = [&](int j) -> int64_t { return boffs[j]; };
+  auto request_k_at = [&](int64_t off, int slot) { dma_1k(pool + off, voff_k, dma_lds + slot * kSlot); };
+  auto request_v_at = [&](int64_t off, int slot) {
+    dma_1k(pool + half_b + off, voff_v, dma_lds + kVBase + slot * kSlot);
   };
-  auto request_v_at = [&](const Pair& pr, int slot) {
-    dma_1k(pool + half_b + pr.b0, voff_v, dma_lds + kVBase + slot * kSlot);
-    dma_1k(pool + half_b + pr.b1, voff_v, dma_lds + kVBase + slot * kSlot + 4096);
-  };
-  auto request_k = [&](int j) { request_k_at(fetch_pair(j), j & (kRing - 1)); };
-  auto request_v = [&](int j) { request_v_at(fetch_pair(j), j & (kRing - 1)); };
+  auto request_k = [&](int j) { request_k_at(fetch_off(j), j & (kRing - 1)); };
+  auto request_v = [&](int j) { request_v_at(fetch_off(j), j & (kRing - 1)); };
   // synchronous variant for the sub-tiles at the end: rows past the context are not fetched,
   // their V is written as zeros so that undefined pool bytes cannot reach the PV product
   auto request_tail = [&](int j) {
-#pragma unroll
-    for (int b = 0; b < 2; b++) {
-      const int64_t boff = boffs[2 * j + b];
-      const bool live = j * kSK + b * 16 + brow < ctx_len;
-      const unsigned l_k = dma_lds + (j & (kRing - 1)) * kSlot + b * 4096;
-      if (live) {
-        dma_1k(pool + boff, voff_k, l_k);
-        dma_1k(pool + boff + half_b, voff_v, l_k + kVBase);
-      } else {
-        *(u32x4*)(smem + (l_k - lds0) + kVBase + (lane << 4)) = (u32x4){0u, 0u, 0u, 0u};
-      }
+    const int64_t boff = fetch_off(j);
+    const bool live = j * kSK + wblk * 16 + brow < ctx_len;
+    const unsigned l_k = dma_lds + (j & (kRing - 1)) * kSlot;
+    if (live) {
+      dma_1k(pool + boff, voff_k, l_k);
+      dma_1k(pool + boff + half_b, voff_v, l_k + kVBase);
+    } else {
+      *(u32x4*)(smem + (l_k - lds0) + kVBase + (lane << 4)) = (u32x4){0u, 0u, 0u, 0u};
     }
   };
 
@@ -289,94 +305,148 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
       }
   };
 
-  // ---- steady step t (t & 3 == T4): QK(t+1), SM(t), PV(t-1) interleaved.
-  Pair ring[4];                                    // block offsets of sub-tiles in flight
-  auto step_steady = [&](auto t4, int t) {
-    constexpr int T4 = decltype(t4)::value;
-    constexpr int C = T4 & 1, N = C ^ 1;             // S/P of sub-tile t live in buffer C
-    constexpr int KS = (T4 + 1) & 3, VS = (T4 + 3) & 3;   // ring slots of K(t+1), V(t-1)
-    if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
-    request_k_at(ring[T4], T4);                      // K(t+4)
-    request_v_at(ring[(T4 + 2) & 3], (T4 + 2) & 3);  // V(t+2)
-    ring[(T4 + 1) & 3] = fetch_pair(t + 5);          // for the next step
-    bf16x8 ka[8];
+  // ---- steady step t (t & 7 == T8): QK(t+1), SM(t), PV(t-1).  MF selects the phase order.
+  // Block offsets for the requests of one unrolled iteration (steps t0 .. t0+7, t0 & 7 == 1):
+  // off_cur[i] belongs to sub-tile t0 + 8 + i, off_prev6/7 to sub-tiles t0 + 6 and t0 + 7.
+  int64_t off_cur[8], off_prev6 = 0, off_prev7 = 0;
+  auto step_steady = [&](auto t8, auto mf, int t) {
+    constexpr int T8 = decltype(t8)::value;
+    constexpr bool MF = decltype(mf)::value != 0;
+    constexpr int I = (T8 + 7) & 7;                  // position inside the unrolled iteration
+    constexpr int C = T8 & 1, N = C ^ 1;             // S/P of sub-tile t live in buffer C
+    constexpr int KS = (T8 + 1) & 7, VS = (T8 + 7) & 7;   // ring slots of K(t+1), V(t-1)
+    request_k_at(off_cur[I], T8);                                                   // K(t+8)
+    request_v_at(I == 0 ? off_prev6 : I == 1 ? off_prev7 : off_cur[(I + 6) & 7], (T8 + 6) & 7);   // V(t+6)
+    // The step has two halves separated by a workgroup barrier.  Waves 0-3 run the softmax of
+    // sub-tile t in the first half and the 16 MFMAs (QK(t+1), PV(t-1)) in the second; waves 4-7,
+    // which share their SIMDs, do the opposite, so in each half one wave of a SIMD owns the
+    // matrix pipe and the other the vector ALU.  The empty asm statements tie the inputs and
+    // results of each half to its side of the barrier: the compiler may not move them across.
+    auto valu_half = [&]() {
+      pin(m_run);
+      float alpha, mc, ps = 0.f;
+      bool changed;
+      sm_head(sbuf[C], alpha, changed, mc);
+      unsigned pk[8];
 #pragma unroll
-    for (int k = 0; k < 8; k++) ka[k] = read_k(ka_addr[k] + KS * kSlot);
-    float alpha, mc, ps = 0.f;
-    bool changed;
-    sm_head(sbuf[C], alpha, changed, mc);
-    unsigned pk[8];
+      for (int e = 0; e < 8; e++) pk[e] = sm_pair(sbuf[C], e, mc, ps);
+      l_run = l_run * alpha + ps;
+      pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+      pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+      al[C] = alpha;
+      chg[C] = changed;
+      pin(pbuf[C][0]);
+      pin(pbuf[C][1]);
+      pin(l_run);
+    };
+    auto mfma_half = [&]() {
+      pin(qB[0]);
+      pin(pbuf[N][0]);
+      pin(pbuf[N][1]);
+      if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
+      bf16x8 ka[8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) pk[e] = sm_pair(sbuf[C], e, mc, ps);
-    f32x16 z;
+      for (int k = 0; k < 8; k++) ka[k] = read_k(ka_addr[k] + KS * kSlot);
+      f32x16 z;
 #pragma unroll
-    for (int r = 0; r < 16; r++) z[r] = 0.f;
-    f32x16 sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
+      for (int r = 0; r < 16; r++) z[r] = 0.f;
+      f32x16 sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
 #pragma unroll
-    for (int k = 1; k < 8; k++) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
+      for (int k = 1; k < 8; k++) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
 #pragma unroll
-    for (int k = 0; k < 8; k++) {
-      const bf16x8 va = read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
-      o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
+      for (int k = 0; k < 8; k++) {
+        const bf16x8 va = read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
+        o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
+      }
+      sbuf[N] = sn;
+      pin(sbuf[N]);
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) pin(o[dt]);
+    };
+    if constexpr (!MF) {
+      valu_half();
+      __builtin_amdgcn_s_barrier();
+      mfma_half();
+    } else {
+      mfma_half();
+      __builtin_amdgcn_s_barrier();
+      valu_half();
     }
-    sbuf[N] = sn;
-    l_run = l_run * alpha + ps;
-    pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
-    pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
-    al[C] = alpha;
-    chg[C] = changed;
-    // Order for the machine scheduler: the wave alternates between a vector-ALU phase (softmax of
-    // sub-tile t, with the K operands of QK(t+1) already on their way from LDS) and an MFMA phase
-    // (QK(t+1) while the V operands arrive, then PV(t-1)); the second wave of the SIMD runs the
-    // opposite phase.
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: K operands
-    __builtin_amdgcn_sched_group_barrier(0x402, 96, 0);   // VALU + TRANS: the whole softmax
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: first four V operands
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);    // MFMA
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // DS read: last four V operands
-    __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);   // MFMA
-    wait_vm<8>();          // everything but the 8 requests of this and the previous step has landed
+    wait_vm<12>();         // everything but the 12 requests of the last six steps has landed
     __syncthreads();
   };
 
   // fill and drain of the pipeline: same three parts, each guarded, one after the other
   auto step_edge = [&](auto par, int t) {
     constexpr int C = decltype(par)::value, N = C ^ 1;
-    request_k(t + 4);
-    request_v(t + 2);
-    if (t + 1 < n_pipe) qk((t + 1) & 3, sbuf[N]);
+    request_k(t + 8);
+    request_v(t + 6);
+    if (t + 1 < n_pipe) qk((t + 1) & 7, sbuf[N]);
     if (t >= 1 && t <= n_pipe) {
       if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
-      pv((t - 1) & 3, pbuf[N]);
+      pv((t - 1) & 7, pbuf[N]);
     }
     if (t < n_pipe) sm_all(sbuf[C], pbuf[C], al[C], chg[C]);
     wait_vm<0>();
     __syncthreads();
   };
 
-  // ---- prologue: K(0..3), V(0..1) resident, S_0 computed
+  // ---- prologue: K(0..7), V(0..5) resident, S_0 computed
 #pragma unroll
-  for (int j = 0; j < 4; j++) request_k(j);
-  request_v(0);
-  request_v(1);
+  for (int j = 0; j < 8; j++) request_k(j);
+#pragma unroll
+  for (int j = 0; j < 6; j++) request_v(j);
   wait_vm<0>();
   __syncthreads();
   if (n_pipe > 0) qk(0, sbuf[0]);
+  __syncthreads();   // step 0 requests K(8) into the slot QK(0) has just read
 
   int t = 0;
   step_edge(Tag<0>{}, t++);                                   // t = 0: QK(1), SM(0)
-  if (t + 4 < n_pipe) {
+  if (t + 8 < n_pipe) {
     // steady steps need 1 <= t and t + 1 < n_pipe; the unrolled loop is entered at t = 1 with the
-    // block offsets of sub-tiles t+2, t+3, t+4 in their ring entries
-    ring[3] = fetch_pair(t + 2);
-    ring[0] = fetch_pair(t + 3);
-    ring[1] = fetch_pair(t + 4);
-    ring[2] = ring[1];
-    for (; t + 4 < n_pipe; t += 4) {
-      step_steady(Tag<1>{}, t);
-      step_steady(Tag<2>{}, t + 1);
-      step_steady(Tag<3>{}, t + 2);
-      step_steady(Tag<0>{}, t + 3);
+    // block offsets of sub-tiles t+6 .. t+15 at hand; each iteration fetches the next eight
+    off_prev6 = fetch_off(t + 6);
+    off_prev7 = fetch_off(t + 7);
+#pragma unroll
+    for (int i = 0; i < 8; i++) off_cur[i] = fetch_off(t + 8 + i);
+    int64_t off_nxt[8];
+    auto fetch_next = [&](int t0) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) off_nxt[i] = fetch_off(t0 + 16 + i);
+    };
+    auto rotate = [&]() {
+      off_prev6 = off_cur[6];
+      off_prev7 = off_cur[7];
+#pragma unroll
+      for (int i = 0; i < 8; i++) off_cur[i] = off_nxt[i];
+    };
+    if (wave < 4) {
+      for (; t + 8 < n_pipe; t += 8) {
+        fetch_next(t);
+        step_steady(Tag<1>{}, Tag<0>{}, t);
+        step_steady(Tag<2>{}, Tag<0>{}, t + 1);
+        step_steady(Tag<3>{}, Tag<0>{}, t + 2);
+        step_steady(Tag<4>{}, Tag<0>{}, t + 3);
+        step_steady(Tag<5>{}, Tag<0>{}, t + 4);
+        step_steady(Tag<6>{}, Tag<0>{}, t + 5);
+        step_steady(Tag<7>{}, Tag<0>{}, t + 6);
+        step_steady(Tag<0>{}, Tag<0>{}, t + 7);
+        rotate();
+      }
+    } else {
+      for (; t + 8 < n_pipe; t += 8) {
+        fetch_next(t);
+        step_steady(Tag<1>{}, Tag<1>{}, t);
+        step_steady(Tag<2>{}, Tag<1>{}, t + 1);
+        step_steady(Tag<3>{}, Tag<1>{}, t + 2);
+        step_steady(Tag<4>{}, Tag<1>{}, t + 3);
+        step_steady(Tag<5>{}, Tag<1>{}, t + 4);
+        step_steady(Tag<6>{}, Tag<1>{}, t + 5);
+        step_steady(Tag<7>{}, Tag<1>{}, t + 6);
+        step_steady(Tag<0>{}, Tag<1>{}, t + 7);
+        rotate();
+      }
     }
   }
   for (; t <= n_pipe; t++) {                                  // remaining pipelined steps and drain
@@ -392,7 +462,7 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
     const int k0 = j * kSK;
     if (wave_active && k0 <= pq_max) {
       f32x16 s;
-      qk(j & 3, s);
+      qk(j & 7, s);
       if (k0 + 31 > pq_min) {
         const int pq = pq_min + ln;
 #pragma unroll
@@ -406,7 +476,7 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
       bool changed;
       sm_all(s, pb, alpha, changed);
       if (__builtin_amdgcn_ballot_w64(changed) != 0) rescale(alpha);
-      pv(j & 3, pb);
+      pv(j & 7, pb);
     }
     __syncthreads();
   }
@@ -437,7 +507,7 @@ __global__ void __launch_bounds__(256, 2) attn_pipe_kernel(AttnParams p) {
 
 }  // namespace pipe
 
-int attn_pipe_tile_tokens(int heads_per_wg) { return 32 * (4 / heads_per_wg); }
+int attn_pipe_tile_tokens(int heads_per_wg) { return 32 * (8 / heads_per_wg); }
 
 hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
@@ -449,7 +519,7 @@ hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream) {
     attr_set = true;
   }
   const unsigned grid = (unsigned)p.n_items * (unsigned)(p.n_q_heads / p.heads_per_wg);
-  hipLaunchKernelGGL(pipe::attn_pipe_kernel, dim3(grid), dim3(256), pipe::kLdsBytes, stream, p);
+  hipLaunchKernelGGL(pipe::attn_pipe_kernel, dim3(grid), dim3(512), pipe::kLdsBytes, stream, p);
   return hipGetLastError();
 }
 

@@ -408,10 +408,12 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const int tile_tokens = mfma ? attn_mfma_tile_tokens(HW) : 1;
 
   // ---- descriptor blob: requests, work items (heaviest first), block tables, block byte offsets.
-  // Each request's table is followed by kTablePad copies of its last entry so that a kernel may
-  // look a few blocks past the end without clamping; blk_offs holds slot * block_bytes (the byte
-  // offset of the block inside a layer of the pool) for the same indices.
-  constexpr int kTablePad = 16;
+  // Each request's table is followed by copies of its last entry (kTablePad of them, one more if
+  // that makes the count even) so that a kernel may look kTablePad blocks past the end without
+  // clamping.  blk_offs holds slot * block_bytes (the byte offset of the block inside a layer of
+  // the pool) for the same blocks, split by parity: first the offsets of blocks 0, 2, 4, ... then
+  // those of blocks 1, 3, 5, ... - a wave that always fetches the same half of a 32-key sub-tile
+  // reads its offsets from consecutive addresses.
   std::vector<int32_t> blob;
   blob.reserve(4 * n_reqs + 1024);
   size_t n_tab = 0;
@@ -421,7 +423,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     blob.push_back(reqs[r].n_prefix_blocks * kBlockTokens);
     blob.push_back(reqs[r].suffix_len);
     blob.push_back(cu_suffix[r]);
-    n_tab += (size_t)nt + kTablePad;
+    n_tab += (size_t)nt + kTablePad + (nt & 1);
   }
   struct Item { int32_t req, tile; int64_t cost; };
   std::vector<Item> items;
@@ -440,14 +442,23 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   for (int r = 0; r < n_reqs; r++) {
     const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
     blob.insert(blob.end(), reqs[r].block_table, reqs[r].block_table + nt);
-    blob.insert(blob.end(), kTablePad, nt > 0 ? reqs[r].block_table[nt - 1] : 0);
+    blob.insert(blob.end(), kTablePad + (nt & 1), nt > 0 ? reqs[r].block_table[nt - 1] : 0);
   }
   if (blob.size() & 1) blob.push_back(0);                       // 8-byte alignment of the offsets
   const size_t offs_off = blob.size();
-  for (size_t i = 0; i < n_tab; i++) {
-    const int64_t off = (int64_t)blob[tables_off + i] * (int64_t)c->blk_bytes;
-    blob.push_back((int32_t)(uint32_t)(off & 0xffffffff));
-    blob.push_back((int32_t)(off >> 32));
+  {
+    size_t base = tables_off;
+    for (int r = 0; r < n_reqs; r++) {
+      const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
+      const size_t padded = (size_t)nt + kTablePad + (nt & 1);
+      for (int par = 0; par < 2; par++)
+        for (size_t i = par; i < padded; i += 2) {
+          const int64_t off = (int64_t)blob[base + i] * (int64_t)c->blk_bytes;
+          blob.push_back((int32_t)(uint32_t)(off & 0xffffffff));
+          blob.push_back((int32_t)(off >> 32));
+        }
+      base += padded;
+    }
   }
 
   rc = ensure_att_blob(c, blob.size());

@@ -26,8 +26,8 @@ struct AttnParams {
   const void* pool_layer;   // this layer's [pool_blocks][2][B][Hkv][D]
   const ReqDesc* reqs;
   const WorkItem* items;
-  const int32_t* tables;    // per request: its block table, then 16 copies of the last entry
-  const int64_t* blk_offs;  // same indexing: slot * block_bytes
+  const int32_t* tables;    // per request: its block table, padded with copies of the last entry
+  const int64_t* blk_offs;  // per request: slot * block_bytes of the even blocks, then of the odd blocks
   int32_t n_items;          // tiles over all requests
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
@@ -57,5 +57,8 @@ hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
 int attn_pipe_tile_tokens(int heads_per_wg);
 
 constexpr int kBlockTokens = 16;
+// Entries appended to every request's device-side block table (copies of its last entry): the
+// pipelined attention kernel requests blocks up to 2 * (ring depth + 1) + 2 past the last one.
+constexpr int kTablePad = 32;
 
 }  // namespace calvo

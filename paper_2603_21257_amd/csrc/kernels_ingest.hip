@@ -13,41 +13,48 @@ namespace calvo {
 
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
+// Kept to a couple of dozen registers (32-bit chunk arithmetic, two loads in flight): its waves
+// must fit into the 32 registers per SIMD lane that the attention kernel leaves free, otherwise
+// the loading stage stalls whenever attention occupies every CU.
 __global__ void __launch_bounds__(256)
 scatter_blocks_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ pool_layer,
-                      const int32_t* __restrict__ table, int64_t n_chunks, int32_t chunks_per_block) {
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n_chunks; i += 4 * stride) {
-    u32x4 v[4];
-    int64_t dst[4];
-#pragma unroll
-    for (int u = 0; u < 4; u++) {
-      const int64_t c = i + u * stride;
-      v[u] = __builtin_nontemporal_load(src + c);
-      const int64_t j = c / chunks_per_block;
-      dst[u] = (int64_t)table[j] * chunks_per_block + (c - j * chunks_per_block);
-    }
-#pragma unroll
-    for (int u = 0; u < 4; u++) pool_layer[dst[u]] = v[u];
+                      const int32_t* __restrict__ table, uint32_t n_chunks, uint32_t chunks_per_block) {
+  const uint32_t stride = gridDim.x * 256u;
+  uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  for (; i + stride < n_chunks; i += 2 * stride) {
+    const uint32_t i1 = i + stride;
+    const u32x4 v0 = __builtin_nontemporal_load(src + i);
+    const u32x4 v1 = __builtin_nontemporal_load(src + i1);
+    const uint32_t j0 = i / chunks_per_block, j1 = i1 / chunks_per_block;
+    pool_layer[(uint64_t)(uint32_t)table[j0] * chunks_per_block + (i - j0 * chunks_per_block)] = v0;
+    pool_layer[(uint64_t)(uint32_t)table[j1] * chunks_per_block + (i1 - j1 * chunks_per_block)] = v1;
   }
-  for (; i < n_chunks; i += stride) {
-    const int64_t j = i / chunks_per_block;
-    pool_layer[(int64_t)table[j] * chunks_per_block + (i - j * chunks_per_block)] = __builtin_nontemporal_load(src + i);
+  if (i < n_chunks) {
+    const uint32_t j = i / chunks_per_block;
+    pool_layer[(uint64_t)(uint32_t)table[j] * chunks_per_block + (i - j * chunks_per_block)] =
+        __builtin_nontemporal_load(src + i);
   }
 }
 
+// One launch moves at most 2^31 16-byte chunks (32 GiB); larger requests are split.
 hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_t* table, int64_t n_blocks,
                                  int32_t blk_bytes, int grid, hipStream_t stream) {
   if (n_blocks <= 0) return hipSuccess;
-  const int32_t cpb = blk_bytes / 16;
-  const int64_t n_chunks = n_blocks * cpb;
-  int64_t need = (n_chunks + 255) / 256;
-  if (grid > need) grid = (int)need;
-  if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(scatter_blocks_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4*)src,
-                     (u32x4*)pool_layer, table, n_chunks, cpb);
-  return hipGetLastError();
+  const int64_t cpb = blk_bytes / 16;
+  const int64_t max_blocks = ((int64_t)1 << 31) / cpb;
+  for (int64_t b0 = 0; b0 < n_blocks; b0 += max_blocks) {
+    const int64_t nb = n_blocks - b0 < max_blocks ? n_blocks - b0 : max_blocks;
+    const int64_t n_chunks = nb * cpb;
+    int64_t need = (n_chunks + 511) / 512;
+    int g = grid > need ? (int)need : grid;
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(scatter_blocks_kernel, dim3(g), dim3(256), 0, stream,
+                       (const u32x4*)((const unsigned char*)src + b0 * blk_bytes), (u32x4*)pool_layer, table + b0,
+                       (uint32_t)n_chunks, (uint32_t)cpb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // Suffix token i of request r sits at absolute position P_r + i: slot table_r[pos / 16],
