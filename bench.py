@@ -28,6 +28,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
+# HBM bytes of one attention launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in
+# profiles/attn_pipe_kernel_cfg3.md (calibrated against the scatter kernel, a plain copy of known size).
+# Counters cannot be read from inside this process, so the figure is carried over from that profile.
+PROFILED_HBM_BYTES_PER_LAUNCH = {3: 645.3e6}
 
 
 def log(*a):
@@ -48,7 +52,7 @@ def main():
     ap.add_argument("--n-staging", type=int, default=0)
     ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sample-rows", type=int, default=256)
+    ap.add_argument("--sample-rows", type=int, default=512)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -182,8 +186,9 @@ def main():
                           "frac_of_bf16_mfma_peak": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
             "overlap": round(overlap, 4),
             "roofline": {"bound": "mfma", "achieved": round(att_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                         "kernel": "attn_mfma_kernel", "flop_per_launch": flop_per_launch,
+                         "unit": "TFLOP/s", "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "traffic": PROFILED_HBM_BYTES_PER_LAUNCH.get(args.config),
+                         "kernel": "calvo::pipe::attn_pipe_kernel", "flop_per_launch": flop_per_launch,
                          "avg_launch_ms": round(k_ms, 4)},
         }
         if not args.no_cpu_baseline:
