@@ -74,7 +74,9 @@ def main():
 
     # ---- resident inputs
     t_setup = time.perf_counter()
-    host = torch.empty((L, w.host_blocks, s.blk_elems), dtype=tdt, pin_memory=True)
+    from paper_2603_21257_amd import hostmem
+    arena = hostmem.PinnedBuffer(L * w.host_blocks * s.blk_bytes)       # exact size, page-locked
+    host = arena.tensor((L, w.host_blocks, s.blk_elems), tdt)
     wl.fill_normal_(host, w.seed + 10)
     pool = torch.empty((L, s.pool_blocks, s.blk_elems), dtype=tdt, device=dev)
     q = wl.fill_normal_(torch.empty((L, T, s.n_q_heads, s.head_dim), dtype=tdt, device=dev), w.seed + 11)
