@@ -350,11 +350,11 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       f32x16 z;
 #pragma unroll
       for (int r = 0; r < 16; r++) z[r] = 0.f;
-      f32x16 sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
-#pragma unroll
-      for (int k = 1; k < 8; k++) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
+      // QK and PV alternate: consecutive MFMAs never wait on each other's accumulator
+      f32x16 sn = z;
 #pragma unroll
       for (int k = 0; k < 8; k++) {
+        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
         const bf16x8 va = read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
         o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
       }
