@@ -61,6 +61,18 @@ constexpr int kLdsBytes = 2 * kRing * kSlot;   // 131072: one 8-wave workgroup p
 
 template <int V>
 struct Tag { static constexpr int value = V; };
+// f(Tag<B>{}), f(Tag<B+1>{}), ... f(Tag<E-1>{}): a loop whose index is a compile-time constant
+template <int B, int E, typename F>
+__device__ inline void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(Tag<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+#ifndef CALVO_PD
+#define CALVO_PD 4
+#endif
+constexpr int kPD = CALVO_PD;   // LDS operand reads run this many MFMAs ahead
 
 // lanes [32,64) of a <-> lanes [0,32) of b (the compiler builtin for this instruction returns
 // its first result twice, hence inline asm)
@@ -309,6 +321,41 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   // Block offsets for the requests of one unrolled iteration (steps t0 .. t0+7, t0 & 7 == 1):
   // off_cur[i] belongs to sub-tile t0 + 8 + i, off_prev6/7 to sub-tiles t0 + 6 and t0 + 7.
   int64_t off_cur[8], off_prev6 = 0, off_prev7 = 0;
+#ifdef CALVO_PHASE_PROF
+  // One phase per build (CALVO_PHASE_PROF = phase index 0..5, or 6 for the whole step): two
+  // scalar registers, so the instrumented kernel keeps the register allocation of the real one.
+  unsigned prof_prev = 0, prof_acc = 0;
+#define PROF(i)                                                                                  \
+  {                                                                                              \
+    if ((i) == (CALVO_PHASE_PROF + 5) % 6 && CALVO_PHASE_PROF < 6) prof_prev = (unsigned)clock64(); \
+    if ((i) == CALVO_PHASE_PROF || ((i) == 5 && CALVO_PHASE_PROF == 6)) {                         \
+      const unsigned tn_ = (unsigned)clock64();                                                  \
+      prof_acc += tn_ - prof_prev;                                                               \
+      prof_prev = tn_;                                                                           \
+    }                                                                                            \
+  }
+#else
+#define PROF(i)
+#endif
+  // first kPD MFMA operands of the coming MFMA half (see step_steady)
+  bf16x8 pre[kPD];
+  auto load_opnd = [&](auto idx, auto ks, auto vs) -> bf16x8 {
+    constexpr int i = decltype(idx)::value, k = i >> 1;
+    constexpr int KS = decltype(ks)::value, VS = decltype(vs)::value;
+    if constexpr (i & 1) return read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
+    else return read_k(ka_addr[k] + KS * kSlot);
+  };
+  auto prefetch = [&](auto ks, auto vs) {
+#ifdef CALVO_SKIP_MFMA
+    return;
+#endif
+    static_for<0, kPD>([&](auto idx) { pre[decltype(idx)::value] = load_opnd(idx, ks, vs); });
+  };
+#ifdef CALVO_NO_MID_BARRIER
+#define MID_BARRIER
+#else
+#define MID_BARRIER __builtin_amdgcn_s_barrier();
+#endif
   auto step_steady = [&](auto t8, auto mf, int t) {
     constexpr int T8 = decltype(t8)::value;
     constexpr bool MF = decltype(mf)::value != 0;
@@ -317,12 +364,16 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     constexpr int KS = (T8 + 1) & 7, VS = (T8 + 7) & 7;   // ring slots of K(t+1), V(t-1)
     request_k_at(off_cur[I], T8);                                                   // K(t+8)
     request_v_at(I == 0 ? off_prev6 : I == 1 ? off_prev7 : off_cur[(I + 6) & 7], (T8 + 6) & 7);   // V(t+6)
+    PROF(0)
     // The step has two halves separated by a workgroup barrier.  Waves 0-3 run the softmax of
     // sub-tile t in the first half and the 16 MFMAs (QK(t+1), PV(t-1)) in the second; waves 4-7,
     // which share their SIMDs, do the opposite, so in each half one wave of a SIMD owns the
     // matrix pipe and the other the vector ALU.  The empty asm statements tie the inputs and
     // results of each half to its side of the barrier: the compiler may not move them across.
     auto valu_half = [&]() {
+#ifdef CALVO_SKIP_VALU
+      return;
+#endif
       pin(m_run);
       float alpha, mc, ps = 0.f;
       bool changed;
@@ -339,41 +390,67 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pin(pbuf[C][1]);
       pin(l_run);
     };
+    // The 16 MFMAs of a step alternate QK_k and PV_k (consecutive MFMAs never share an
+    // accumulator); operand i is K chunk i/2 (i even) or V^T chunk i/2 (i odd), read from LDS
+    // kPD operands ahead of the MFMA that consumes it.  The first kPD operands (pre[]) are read
+    // by prefetch() well before the MFMA half starts, so no LDS latency is exposed.
+    bf16x8 opnd[16];
     auto mfma_half = [&]() {
+#ifdef CALVO_SKIP_MFMA
+      return;
+#endif
       pin(qB[0]);
       pin(pbuf[N][0]);
       pin(pbuf[N][1]);
       if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
-      bf16x8 ka[8];
+#ifdef CALVO_SETPRIO
+      __builtin_amdgcn_s_setprio(CALVO_SETPRIO);
+#endif
+      f32x16 sn;
 #pragma unroll
-      for (int k = 0; k < 8; k++) ka[k] = read_k(ka_addr[k] + KS * kSlot);
-      f32x16 z;
-#pragma unroll
-      for (int r = 0; r < 16; r++) z[r] = 0.f;
-      // QK and PV alternate: consecutive MFMAs never wait on each other's accumulator
-      f32x16 sn = z;
-#pragma unroll
-      for (int k = 0; k < 8; k++) {
-        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[k], qB[k], sn, 0, 0, 0);
-        const bf16x8 va = read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
-        o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
-      }
+      for (int r = 0; r < 16; r++) sn[r] = 0.f;
+      static_for<0, kPD>([&](auto idx) { opnd[decltype(idx)::value] = pre[decltype(idx)::value]; });
+      static_for<0, 16>([&](auto idx) {
+        constexpr int i = decltype(idx)::value, k = i >> 1;
+        if constexpr (i & 1) o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], pbuf[N][k >> 2], o[k & 3], 0, 0, 0);
+        else sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], qB[k], sn, 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (i + kPD < 16) {
+          opnd[i + kPD] = load_opnd(Tag<i + kPD>{}, Tag<KS>{}, Tag<VS>{});
+          __builtin_amdgcn_sched_group_barrier(0x100, ((i + kPD) & 1) ? 2 : 1, 0);
+        }
+      });
+#ifdef CALVO_SETPRIO
+      __builtin_amdgcn_s_setprio(0);
+#endif
       sbuf[N] = sn;
       pin(sbuf[N]);
 #pragma unroll
       for (int dt = 0; dt < 4; dt++) pin(o[dt]);
     };
     if constexpr (!MF) {
+      prefetch(Tag<KS>{}, Tag<VS>{});          // lands while the softmax runs
       valu_half();
-      __builtin_amdgcn_s_barrier();
+      PROF(1)
+      MID_BARRIER
+      PROF(2)
       mfma_half();
+      PROF(3)
     } else {
-      mfma_half();
-      __builtin_amdgcn_s_barrier();
+      mfma_half();                             // pre[] was read at the end of the previous step
+      PROF(1)
+      MID_BARRIER
+      PROF(2)
       valu_half();
+      prefetch(Tag<(KS + 1) & 7>{}, Tag<(VS + 1) & 7>{});   // K(t+2), V(t): first operands of step t+1
+      PROF(3)
     }
-    wait_vm<12>();         // everything but the 12 requests of the last six steps has landed
+    // Everything but the 10 requests of the last five steps has landed, i.e. K up to t+3 and V
+    // up to t+1: what step t+1 reads, and what waves 4-7 prefetch at the end of step t+1.
+    wait_vm<10>();
+    PROF(4)
     __syncthreads();
+    PROF(5)
   };
 
   // fill and drain of the pipeline: same three parts, each guarded, one after the other
@@ -421,6 +498,9 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #pragma unroll
       for (int i = 0; i < 8; i++) off_cur[i] = off_nxt[i];
     };
+#ifdef CALVO_PHASE_PROF
+    prof_prev = (unsigned)clock64();
+#endif
     if (wave < 4) {
       for (; t + 8 < n_pipe; t += 8) {
         fetch_next(t);
@@ -435,6 +515,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
         rotate();
       }
     } else {
+      prefetch(Tag<2>{}, Tag<0>{});                          // K(2), V(0) for step 1
       for (; t + 8 < n_pipe; t += 8) {
         fetch_next(t);
         step_steady(Tag<1>{}, Tag<1>{}, t);
@@ -449,6 +530,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       }
     }
   }
+#ifdef CALVO_PHASE_PROF
+  if (lane == 0 && p.prof)
+    p.prof[(long long)blockIdx.x * 8 + wave] = prof_acc;
+#endif
   for (; t <= n_pipe; t++) {                                  // remaining pipelined steps and drain
     if (t & 1) step_edge(Tag<1>{}, t);
     else step_edge(Tag<0>{}, t);

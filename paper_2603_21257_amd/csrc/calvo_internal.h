@@ -33,6 +33,7 @@ struct AttnParams {
   int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
   int32_t tile_tokens;      // suffix tokens per work item
   float scale;              // softmax scale (natural-exponent units)
+  long long* prof;          // phase-timing builds only (CALVO_PHASE_PROF): one counter per wave, else NULL
 };
 
 struct AppendParams {
