@@ -57,6 +57,7 @@ constexpr int kVBase = kRing * kSlot;          // V ring follows the K ring
 // half the number of real blocks (rounded up); each parity half of the padded table holds
 // (real blocks + kTablePad) / 2 entries
 static_assert(kTablePad >= 4 * kRing, "block table padding too small for the ring depth");
+constexpr float kLazyBound = 65536.f;   // a lane's partial row sum of 16 weights may reach 2^16 before the reference is raised
 constexpr int kLdsBytes = 2 * kRing * kSlot;   // 131072: one 8-wave workgroup per CU
 
 template <int V>
@@ -71,6 +72,16 @@ __device__ inline void static_for(F&& f) {
 }
 #ifndef CALVO_PD
 #define CALVO_PD 4
+#endif
+#ifdef CALVO_PAIRED
+constexpr bool kPaired = true;
+#else
+constexpr bool kPaired = false;
+#endif
+#ifdef CALVO_EARLY_REQUESTS
+constexpr bool kLateRequests = false;
+#else
+constexpr bool kLateRequests = true;
 #endif
 constexpr int kPD = CALVO_PD;   // LDS operand reads run this many MFMAs ahead
 
@@ -103,7 +114,15 @@ __device__ inline void dma_1k(const unsigned char* sbase, unsigned voff, unsigne
 // point and its consumers below it; emits no instruction
 template <typename T>
 __device__ inline void pin(T& x) {
+#ifndef CALVO_NO_PINS
   asm volatile("" : "+v"(x));
+#endif
+}
+// the compiler moves no instruction across this point; emits nothing and waits for nothing
+__device__ inline void phase_fence() {
+#ifdef CALVO_NO_PINS
+  __builtin_amdgcn_sched_barrier(0);
+#endif
 }
 template <int N>
 __device__ inline void wait_vm() {
@@ -176,7 +195,9 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
   const float c2 = p.scale * 1.4426950408889634f;
 
-  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8]
+  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8],
+  // multiplied by scale * log2(e) and rounded to bf16 again, so that the MFMA accumulators hold
+  // the scores in the base-2 exponent domain and the softmax needs no multiply per score
   bf16x8 qB[8];
   {
     const unsigned short* q = (const unsigned short*)p.q;
@@ -187,7 +208,15 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     for (int ks = 0; ks < 8; ks++) {
       u32x4 v = {0u, 0u, 0u, 0u};
       if (ok) v = *(const u32x4*)(row + 16 * ks);
-      qB[ks] = __builtin_bit_cast(bf16x8, v);
+      u32x4 w;
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        bf16x2 pk;
+        pk[0] = (__bf16)(__builtin_bit_cast(float, v[j] << 16) * c2);
+        pk[1] = (__bf16)(__builtin_bit_cast(float, v[j] & 0xffff0000u) * c2);
+        w[j] = __builtin_bit_cast(unsigned, pk);
+      }
+      qB[ks] = __builtin_bit_cast(bf16x8, w);
     }
   }
 
@@ -196,6 +225,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   for (int dt = 0; dt < 4; dt++)
 #pragma unroll
     for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+  // Softmax state per query (base-2 exponent domain): O and l_run are sums of weights
+  // 2^(score - m_run).  In the steady loop m_run is a reference that is only raised when a lane's
+  // partial row sum would pass kLazyBound; it is always the exact maximum of some earlier
+  // sub-tile, so the largest weight of a row is at least 1 and nothing underflows.
   float m_run = -INFINITY, l_run = 0.f;
 
   // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches rows 4(w&3)..+3 of block
@@ -281,16 +314,16 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
     mx = half_swap_max(mx);
     const float m_new = fmaxf(m_run, mx);
-    alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     changed = (m_new != m_run);
     m_run = m_new;
-    mc = m_new * c2;
+    mc = m_new;
   };
   // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the rounded
   // values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
   auto sm_pair = [&](const f32x16& s, int e, float mc, float& ps) -> unsigned {
-    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, -mc));
-    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, -mc));
+    const float p0 = __builtin_amdgcn_exp2f(s[2 * e] - mc);
+    const float p1 = __builtin_amdgcn_exp2f(s[2 * e + 1] - mc);
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
@@ -319,8 +352,8 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 
   // ---- steady step t (t & 7 == T8): QK(t+1), SM(t), PV(t-1).  MF selects the phase order.
   // Block offsets for the requests of one unrolled iteration (steps t0 .. t0+7, t0 & 7 == 1):
-  // off_cur[i] belongs to sub-tile t0 + 8 + i, off_prev6/7 to sub-tiles t0 + 6 and t0 + 7.
-  int64_t off_cur[8], off_prev6 = 0, off_prev7 = 0;
+  // off_cur[i] belongs to sub-tile t0 + 8 + i, off_prev5/6/7 to sub-tiles t0 + 5, t0 + 6, t0 + 7.
+  int64_t off_cur[8], off_prev5 = 0, off_prev6 = 0, off_prev7 = 0;
 #ifdef CALVO_PHASE_PROF
   // One phase per build (CALVO_PHASE_PROF = phase index 0..5, or 6 for the whole step): two
   // scalar registers, so the instrumented kernel keeps the register allocation of the real one.
@@ -337,6 +370,15 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #else
 #define PROF(i)
 #endif
+#if defined(CALVO_PHASE_PROF) && CALVO_PHASE_PROF == 8
+  // Timeline build: lane 0 of every wave stamps six events of steps kLogT0 .. kLogT0+15 into the
+  // LDS behind the rings (the launch must ask for kLdsBytes + 8192); copied out at the end.
+  constexpr int kLogT0 = 801;
+#undef PROF
+#define PROF(i)                                                                                  \
+  if ((unsigned)(t - kLogT0) < 16u && lane == 0)                                                 \
+    *(long long*)(smem + kLdsBytes + ((wave * 16 + (t - kLogT0)) * 6 + (i)) * 8) = clock64();
+#endif
   // first kPD MFMA operands of the coming MFMA half (see step_steady)
   bf16x8 pre[kPD];
   auto load_opnd = [&](auto idx, auto ks, auto vs) -> bf16x8 {
@@ -351,10 +393,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #endif
     static_for<0, kPD>([&](auto idx) { pre[decltype(idx)::value] = load_opnd(idx, ks, vs); });
   };
-#ifdef CALVO_NO_MID_BARRIER
-#define MID_BARRIER
-#else
+#ifdef CALVO_MID_BARRIER
 #define MID_BARRIER __builtin_amdgcn_s_barrier();
+#else
+#define MID_BARRIER
 #endif
   auto step_steady = [&](auto t8, auto mf, int t) {
     constexpr int T8 = decltype(t8)::value;
@@ -362,8 +404,27 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     constexpr int I = (T8 + 7) & 7;                  // position inside the unrolled iteration
     constexpr int C = T8 & 1, N = C ^ 1;             // S/P of sub-tile t live in buffer C
     constexpr int KS = (T8 + 1) & 7, VS = (T8 + 7) & 7;   // ring slots of K(t+1), V(t-1)
-    request_k_at(off_cur[I], T8);                                                   // K(t+8)
-    request_v_at(I == 0 ? off_prev6 : I == 1 ? off_prev7 : off_cur[(I + 6) & 7], (T8 + 6) & 7);   // V(t+6)
+    // kPaired: steps run in pairs (t odd, t + 1) between workgroup barriers.  The first step of a
+    // pair requests the sub-tiles both steps would have fetched: K(t+7), K(t+8), V(t+5), V(t+6).
+    // Their ring slots held K(t-1), K(t), V(t-3), V(t-2), which nobody reads after the previous
+    // barrier.  Otherwise every step requests K(t+7) and V(t+5) and ends with a barrier.
+    auto requests = [&]() {
+#ifdef CALVO_SKIP_DMA
+      return;
+#endif
+      if constexpr (kPaired) {
+        if constexpr ((I & 1) == 0) {
+          request_k_at(I == 0 ? off_prev7 : off_cur[(I + 7) & 7], (T8 + 7) & 7);
+          request_k_at(off_cur[I], T8);
+          request_v_at(I == 0 ? off_prev5 : I == 2 ? off_prev7 : off_cur[(I + 5) & 7], (T8 + 5) & 7);
+          request_v_at(I == 0 ? off_prev6 : off_cur[(I + 6) & 7], (T8 + 6) & 7);
+        }
+      } else {
+        request_k_at(I == 0 ? off_prev7 : off_cur[(I + 7) & 7], (T8 + 7) & 7);
+        request_v_at(I == 0 ? off_prev5 : I == 1 ? off_prev6 : I == 2 ? off_prev7 : off_cur[(I + 5) & 7], (T8 + 5) & 7);
+      }
+    };
+    if constexpr (!MF || !kLateRequests) requests();
     PROF(0)
     // The step has two halves separated by a workgroup barrier.  Waves 0-3 run the softmax of
     // sub-tile t in the first half and the 16 MFMAs (QK(t+1), PV(t-1)) in the second; waves 4-7,
@@ -374,21 +435,61 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #ifdef CALVO_SKIP_VALU
       return;
 #endif
+#ifdef CALVO_SM_PRIO
+      __builtin_amdgcn_s_setprio(CALVO_SM_PRIO);
+#endif
+      phase_fence();
       pin(m_run);
-      float alpha, mc, ps = 0.f;
-      bool changed;
-      sm_head(sbuf[C], alpha, changed, mc);
+      const f32x16& s = sbuf[C];
+      float a_acc = 1.f;
+      bool changed = false;
+      float ps;
       unsigned pk[8];
+      // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the
+      // rounded values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
+      auto weights = [&]() {
+        float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; e++) pk[e] = sm_pair(sbuf[C], e, mc, ps);
-      l_run = l_run * alpha + ps;
+        for (int e = 0; e < 8; e++) {
+          bf16x2 w;
+          w[0] = (__bf16)__builtin_amdgcn_exp2f(s[2 * e] - m_run);
+          w[1] = (__bf16)__builtin_amdgcn_exp2f(s[2 * e + 1] - m_run);
+          if (e & 1) ps1 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps1, false);
+          else ps0 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps0, false);
+          pk[e] = __builtin_bit_cast(unsigned, w);
+        }
+        ps = ps0 + ps1;
+      };
+      weights();
+      // Accept unless a partial row sum is above the bound (or not a number).  Otherwise raise the
+      // reference to this sub-tile's maximum, rescale the running sum (O is rescaled at the start
+      // of the next MFMA half through al/chg) and compute the weights again: now all are <= 1.
+      if (__builtin_amdgcn_ballot_w64(!(ps <= kLazyBound)) != 0) {
+#if defined(CALVO_PHASE_PROF) && CALVO_PHASE_PROF == 7
+        prof_acc += 1;                       // this build counts slow-path entries instead of cycles
+#endif
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+        const float m_new = fmaxf(m_run, half_swap_max(mx));
+        a_acc = __builtin_amdgcn_exp2f(m_run - m_new);
+        changed = (m_new != m_run);
+        m_run = m_new;
+        l_run *= a_acc;
+        weights();
+      }
+#ifdef CALVO_SM_PRIO
+      __builtin_amdgcn_s_setprio(0);
+#endif
+      l_run += ps;
       pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
       pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
-      al[C] = alpha;
+      al[C] = a_acc;
       chg[C] = changed;
       pin(pbuf[C][0]);
       pin(pbuf[C][1]);
       pin(l_run);
+      phase_fence();
     };
     // The 16 MFMAs of a step alternate QK_k and PV_k (consecutive MFMAs never share an
     // accumulator); operand i is K chunk i/2 (i even) or V^T chunk i/2 (i odd), read from LDS
@@ -399,6 +500,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #ifdef CALVO_SKIP_MFMA
       return;
 #endif
+      phase_fence();
       pin(qB[0]);
       pin(pbuf[N][0]);
       pin(pbuf[N][1]);
@@ -427,6 +529,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pin(sbuf[N]);
 #pragma unroll
       for (int dt = 0; dt < 4; dt++) pin(o[dt]);
+      phase_fence();
     };
     if constexpr (!MF) {
       prefetch(Tag<KS>{}, Tag<VS>{});          // lands while the softmax runs
@@ -438,6 +541,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       PROF(3)
     } else {
       mfma_half();                             // pre[] was read at the end of the previous step
+      if constexpr (kLateRequests) requests();   // keeps the requests out of the way of the first MFMAs
       PROF(1)
       MID_BARRIER
       PROF(2)
@@ -445,19 +549,31 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       prefetch(Tag<(KS + 1) & 7>{}, Tag<(VS + 1) & 7>{});   // K(t+2), V(t): first operands of step t+1
       PROF(3)
     }
-    // Everything but the 10 requests of the last five steps has landed, i.e. K up to t+3 and V
-    // up to t+1: what step t+1 reads, and what waves 4-7 prefetch at the end of step t+1.
-    wait_vm<10>();
-    PROF(4)
-    __syncthreads();
+    // End of a pair (or step): everything but the requests of this pair (the last four steps) has
+    // landed, i.e. K up to t+5 and V up to t+3 seen from step t: what the steps up to the next
+    // barrier read, and what waves 4-7 prefetch before that barrier.  The barrier also separates
+    // the LDS reads before it from the requests after it into the same ring slots.
+    if constexpr (kPaired) {
+      if constexpr ((I & 1) == 1) {
+        wait_vm<4>();
+        PROF(4)
+        __syncthreads();
+      }
+    } else {
+#ifndef CALVO_SKIP_BARRIER
+      wait_vm<8>();
+      PROF(4)
+      __syncthreads();
+#endif
+    }
     PROF(5)
   };
 
   // fill and drain of the pipeline: same three parts, each guarded, one after the other
   auto step_edge = [&](auto par, int t) {
     constexpr int C = decltype(par)::value, N = C ^ 1;
-    request_k(t + 8);
-    request_v(t + 6);
+    request_k(t + 7);
+    request_v(t + 5);
     if (t + 1 < n_pipe) qk((t + 1) & 7, sbuf[N]);
     if (t >= 1 && t <= n_pipe) {
       if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
@@ -468,21 +584,23 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     __syncthreads();
   };
 
-  // ---- prologue: K(0..7), V(0..5) resident, S_0 computed
+  // ---- prologue: K(0..6), V(0..4) resident, S_0 computed.  From here on K(<= t+6) and V(<= t+4)
+  // have been requested before step t starts.
 #pragma unroll
-  for (int j = 0; j < 8; j++) request_k(j);
+  for (int j = 0; j < 7; j++) request_k(j);
 #pragma unroll
-  for (int j = 0; j < 6; j++) request_v(j);
+  for (int j = 0; j < 5; j++) request_v(j);
   wait_vm<0>();
   __syncthreads();
   if (n_pipe > 0) qk(0, sbuf[0]);
-  __syncthreads();   // step 0 requests K(8) into the slot QK(0) has just read
+  __syncthreads();   // all of QK(0) is done before any wave starts requesting into the ring again
 
   int t = 0;
   step_edge(Tag<0>{}, t++);                                   // t = 0: QK(1), SM(0)
   if (t + 8 < n_pipe) {
     // steady steps need 1 <= t and t + 1 < n_pipe; the unrolled loop is entered at t = 1 with the
     // block offsets of sub-tiles t+6 .. t+15 at hand; each iteration fetches the next eight
+    off_prev5 = fetch_off(t + 5);
     off_prev6 = fetch_off(t + 6);
     off_prev7 = fetch_off(t + 7);
 #pragma unroll
@@ -493,6 +611,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       for (int i = 0; i < 8; i++) off_nxt[i] = fetch_off(t0 + 16 + i);
     };
     auto rotate = [&]() {
+      off_prev5 = off_cur[5];
       off_prev6 = off_cur[6];
       off_prev7 = off_cur[7];
 #pragma unroll
@@ -501,7 +620,16 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #ifdef CALVO_PHASE_PROF
     prof_prev = (unsigned)clock64();
 #endif
+#ifdef CALVO_YOUNG_PRIO
+    if (wave >= 4) __builtin_amdgcn_s_setprio(CALVO_YOUNG_PRIO);
+#endif
+#if defined(CALVO_INPHASE)
+    if (true) {
+#elif defined(CALVO_SWAP_ROLES)
+    if (wave >= 4) {
+#else
     if (wave < 4) {
+#endif
       for (; t + 8 < n_pipe; t += 8) {
         fetch_next(t);
         step_steady(Tag<1>{}, Tag<0>{}, t);
@@ -530,7 +658,11 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       }
     }
   }
-#ifdef CALVO_PHASE_PROF
+#if defined(CALVO_PHASE_PROF) && CALVO_PHASE_PROF == 8
+  if (p.prof && blockIdx.x == 300)
+    for (int i = lane; i < 16 * 6; i += 64)
+      p.prof[wave * 96 + i] = *(long long*)(smem + kLdsBytes + (wave * 96 + i) * 8);
+#elif defined(CALVO_PHASE_PROF)
   if (lane == 0 && p.prof)
     p.prof[(long long)blockIdx.x * 8 + wave] = prof_acc;
 #endif
