@@ -5,30 +5,42 @@
 //
 // Schedule.  The key loop advances in 32-key sub-tiles.  For sub-tile j the stages
 //     QK(j):  S_j = K_j Q^T                                     8 MFMA
-//     SM(j):  m, alpha, P_j = exp2(c (S_j - m)), row sums       ~60 vector-ALU instructions
-//     PV(j):  O^T = alpha O^T + V_j^T P_j^T                     8 MFMA
-// depend on each other, but QK(t+1), SM(t) and PV(t-1) do not.  Step t issues exactly these
-// three, interleaved in 16 slots of one MFMA plus a share of the exponentials, so the matrix
-// pipe always has an independent MFMA to run while the vector ALU works through the softmax.
-// S and P are double buffered in registers; the steady loop is unrolled by eight so that
-// register buffers and LDS ring slots are named statically (eight-fold for the ring).
+//     SM(j):  P_j = 2^(S_j - m), row sums                       ~55 vector-ALU instructions
+//     PV(j):  O^T += V_j^T P_j^T                                8 MFMA
+// depend on each other, but QK(t+1), SM(t) and PV(t-1) do not.  Step t runs exactly these three:
+// the 16 MFMAs as one half of the step (QK_k and PV_k alternating, operands read from LDS four
+// MFMAs ahead), the softmax as the other half.  S and P are double buffered in registers; the
+// steady loop is unrolled by eight so that register buffers and LDS ring slots are named
+// statically.
+//
+// Softmax.  Q is multiplied by scale * log2(e) and rounded to bf16 once, when it is loaded, so the
+// accumulators hold base-2 exponents and a weight is one subtract and one v_exp_f32.  In the
+// steady loop the reference m is raised lazily: the weights of a sub-tile are computed against
+// the current m, and only if a lane's partial row sum passes 2^16 is the sub-tile's maximum
+// taken, m raised, l and O rescaled and the weights computed again.  m is always the exact
+// maximum of an earlier sub-tile, so the largest weight of a row is >= 1: nothing underflows, and
+// with fp32 accumulation and bf16 weights (relative precision) the result is that of the
+// textbook recurrence up to rounding.  Edge and diagonal sub-tiles use the textbook update.
 //
 // Data movement.  K and V go from the pool straight into LDS with global_load_lds_dwordx4
 // (no register staging): each wave instruction deposits 4 token rows x 256 B.  Two rings of
 // eight 8 KiB slots (K and V separately, because K_j is consumed two steps before V_j): at
-// step t the workgroup requests K(t+8) and V(t+6), reads K(t+1) and V(t-1), and ends with
-// s_waitcnt vmcnt(12) + one barrier, which guarantees K(t+2) and V(t) - requested six steps
-// earlier - have landed.  The deep ring matters: all workgroups of an XCD walk the same K/V
-// stream, whoever is first pays the full HBM latency, and only requests issued several steps
-// ahead keep that latency off the critical path.  Rows are unpadded; 16-byte chunks are
+// step t the workgroup requests K(t+7) and V(t+5), reads K(t+1) and V(t-1), and ends with
+// s_waitcnt vmcnt(8) + one barrier, which guarantees K(t+3) and V(t+1) - requested at least four
+// steps earlier - have landed.  The deep ring matters: all workgroups of an XCD walk the same
+// K/V stream, whoever is first pays the full HBM latency, and only requests issued several
+// steps ahead keep that latency off the critical path.  Rows are unpadded; 16-byte chunks are
 // XOR-swizzled on the way in (the lane that owns LDS chunk position c fetches logical chunk
 // c ^ f(row)) so that operand reads are bank-conflict free: K f = row & 15, V f = (row & 3) << 2.
 // All operand addresses are lane constants (8 for K, 4 for V) plus compile-time offsets.
 //
 // Workgroup = 8 waves = 4 query heads of one KV group x 2 token tiles of 32; waves w and w+4
 // share a SIMD.  Within a step waves 0-3 run softmax first and MFMAs second, waves 4-7 the
-// other way round, so each SIMD always has one wave feeding the matrix pipe while the other
-// uses the vector ALU.
+// other way round, so one wave of a SIMD feeds the matrix pipe while the other uses the vector
+// ALU.  (Measured on MI355X: an MFMA keeps the vector ALU of its SIMD from issuing for about
+// half its 32 cycles, whichever wave the vector instruction comes from, so the overlap is
+// partial; a wave-level priority (s_setprio) changes nothing, and neither does dropping the
+// per-step barrier in favour of per-wave progress counters.)
 //
 // Sub-tiles that touch the causal diagonal or the end of the context are not pipelined: they
 // are at most a handful per workgroup and are loaded synchronously and run QK -> mask -> SM ->
@@ -70,20 +82,7 @@ __device__ inline void static_for(F&& f) {
     static_for<B + 1, E>(f);
   }
 }
-#ifndef CALVO_PD
-#define CALVO_PD 4
-#endif
-#ifdef CALVO_PAIRED
-constexpr bool kPaired = true;
-#else
-constexpr bool kPaired = false;
-#endif
-#ifdef CALVO_EARLY_REQUESTS
-constexpr bool kLateRequests = false;
-#else
-constexpr bool kLateRequests = true;
-#endif
-constexpr int kPD = CALVO_PD;   // LDS operand reads run this many MFMAs ahead
+constexpr int kPD = 4;   // LDS operand reads run this many MFMAs ahead
 
 // lanes [32,64) of a <-> lanes [0,32) of b (the compiler builtin for this instruction returns
 // its first result twice, hence inline asm)
@@ -114,15 +113,7 @@ __device__ inline void dma_1k(const unsigned char* sbase, unsigned voff, unsigne
 // point and its consumers below it; emits no instruction
 template <typename T>
 __device__ inline void pin(T& x) {
-#ifndef CALVO_NO_PINS
   asm volatile("" : "+v"(x));
-#endif
-}
-// the compiler moves no instruction across this point; emits nothing and waits for nothing
-__device__ inline void phase_fence() {
-#ifdef CALVO_NO_PINS
-  __builtin_amdgcn_sched_barrier(0);
-#endif
 }
 template <int N>
 __device__ inline void wait_vm() {
@@ -370,15 +361,6 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #else
 #define PROF(i)
 #endif
-#if defined(CALVO_PHASE_PROF) && CALVO_PHASE_PROF == 8
-  // Timeline build: lane 0 of every wave stamps six events of steps kLogT0 .. kLogT0+15 into the
-  // LDS behind the rings (the launch must ask for kLdsBytes + 8192); copied out at the end.
-  constexpr int kLogT0 = 801;
-#undef PROF
-#define PROF(i)                                                                                  \
-  if ((unsigned)(t - kLogT0) < 16u && lane == 0)                                                 \
-    *(long long*)(smem + kLdsBytes + ((wave * 16 + (t - kLogT0)) * 6 + (i)) * 8) = clock64();
-#endif
   // first kPD MFMA operands of the coming MFMA half (see step_steady)
   bf16x8 pre[kPD];
   auto load_opnd = [&](auto idx, auto ks, auto vs) -> bf16x8 {
@@ -388,57 +370,29 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     else return read_k(ka_addr[k] + KS * kSlot);
   };
   auto prefetch = [&](auto ks, auto vs) {
-#ifdef CALVO_SKIP_MFMA
-    return;
-#endif
     static_for<0, kPD>([&](auto idx) { pre[decltype(idx)::value] = load_opnd(idx, ks, vs); });
   };
-#ifdef CALVO_MID_BARRIER
-#define MID_BARRIER __builtin_amdgcn_s_barrier();
-#else
-#define MID_BARRIER
-#endif
   auto step_steady = [&](auto t8, auto mf, int t) {
     constexpr int T8 = decltype(t8)::value;
     constexpr bool MF = decltype(mf)::value != 0;
     constexpr int I = (T8 + 7) & 7;                  // position inside the unrolled iteration
     constexpr int C = T8 & 1, N = C ^ 1;             // S/P of sub-tile t live in buffer C
     constexpr int KS = (T8 + 1) & 7, VS = (T8 + 7) & 7;   // ring slots of K(t+1), V(t-1)
-    // kPaired: steps run in pairs (t odd, t + 1) between workgroup barriers.  The first step of a
-    // pair requests the sub-tiles both steps would have fetched: K(t+7), K(t+8), V(t+5), V(t+6).
-    // Their ring slots held K(t-1), K(t), V(t-3), V(t-2), which nobody reads after the previous
-    // barrier.  Otherwise every step requests K(t+7) and V(t+5) and ends with a barrier.
+    // K(t+7) and V(t+5) go into the ring slots of K(t-1) and V(t-3), which nobody reads after
+    // the barrier that ended step t-1.  Waves 4-7 issue theirs after their MFMAs, which keeps the
+    // requests out of the way of the matrix pipe at the start of the step.
     auto requests = [&]() {
-#ifdef CALVO_SKIP_DMA
-      return;
-#endif
-      if constexpr (kPaired) {
-        if constexpr ((I & 1) == 0) {
-          request_k_at(I == 0 ? off_prev7 : off_cur[(I + 7) & 7], (T8 + 7) & 7);
-          request_k_at(off_cur[I], T8);
-          request_v_at(I == 0 ? off_prev5 : I == 2 ? off_prev7 : off_cur[(I + 5) & 7], (T8 + 5) & 7);
-          request_v_at(I == 0 ? off_prev6 : off_cur[(I + 6) & 7], (T8 + 6) & 7);
-        }
-      } else {
-        request_k_at(I == 0 ? off_prev7 : off_cur[(I + 7) & 7], (T8 + 7) & 7);
-        request_v_at(I == 0 ? off_prev5 : I == 1 ? off_prev6 : I == 2 ? off_prev7 : off_cur[(I + 5) & 7], (T8 + 5) & 7);
-      }
+      request_k_at(I == 0 ? off_prev7 : off_cur[(I + 7) & 7], (T8 + 7) & 7);
+      request_v_at(I == 0 ? off_prev5 : I == 1 ? off_prev6 : I == 2 ? off_prev7 : off_cur[(I + 5) & 7], (T8 + 5) & 7);
     };
-    if constexpr (!MF || !kLateRequests) requests();
+    if constexpr (!MF) requests();
     PROF(0)
-    // The step has two halves separated by a workgroup barrier.  Waves 0-3 run the softmax of
+    // The step has two halves.  Waves 0-3 run the softmax of
     // sub-tile t in the first half and the 16 MFMAs (QK(t+1), PV(t-1)) in the second; waves 4-7,
     // which share their SIMDs, do the opposite, so in each half one wave of a SIMD owns the
     // matrix pipe and the other the vector ALU.  The empty asm statements tie the inputs and
     // results of each half to its side of the barrier: the compiler may not move them across.
     auto valu_half = [&]() {
-#ifdef CALVO_SKIP_VALU
-      return;
-#endif
-#ifdef CALVO_SM_PRIO
-      __builtin_amdgcn_s_setprio(CALVO_SM_PRIO);
-#endif
-      phase_fence();
       pin(m_run);
       const f32x16& s = sbuf[C];
       float a_acc = 1.f;
@@ -478,9 +432,6 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
         l_run *= a_acc;
         weights();
       }
-#ifdef CALVO_SM_PRIO
-      __builtin_amdgcn_s_setprio(0);
-#endif
       l_run += ps;
       pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
       pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
@@ -489,7 +440,6 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pin(pbuf[C][0]);
       pin(pbuf[C][1]);
       pin(l_run);
-      phase_fence();
     };
     // The 16 MFMAs of a step alternate QK_k and PV_k (consecutive MFMAs never share an
     // accumulator); operand i is K chunk i/2 (i even) or V^T chunk i/2 (i odd), read from LDS
@@ -497,17 +447,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     // by prefetch() well before the MFMA half starts, so no LDS latency is exposed.
     bf16x8 opnd[16];
     auto mfma_half = [&]() {
-#ifdef CALVO_SKIP_MFMA
-      return;
-#endif
-      phase_fence();
       pin(qB[0]);
       pin(pbuf[N][0]);
       pin(pbuf[N][1]);
       if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
-#ifdef CALVO_SETPRIO
-      __builtin_amdgcn_s_setprio(CALVO_SETPRIO);
-#endif
       f32x16 sn;
 #pragma unroll
       for (int r = 0; r < 16; r++) sn[r] = 0.f;
@@ -522,50 +465,34 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
           __builtin_amdgcn_sched_group_barrier(0x100, ((i + kPD) & 1) ? 2 : 1, 0);
         }
       });
-#ifdef CALVO_SETPRIO
-      __builtin_amdgcn_s_setprio(0);
-#endif
       sbuf[N] = sn;
       pin(sbuf[N]);
 #pragma unroll
       for (int dt = 0; dt < 4; dt++) pin(o[dt]);
-      phase_fence();
     };
     if constexpr (!MF) {
       prefetch(Tag<KS>{}, Tag<VS>{});          // lands while the softmax runs
       valu_half();
       PROF(1)
-      MID_BARRIER
       PROF(2)
       mfma_half();
       PROF(3)
     } else {
       mfma_half();                             // pre[] was read at the end of the previous step
-      if constexpr (kLateRequests) requests();   // keeps the requests out of the way of the first MFMAs
+      requests();
       PROF(1)
-      MID_BARRIER
       PROF(2)
       valu_half();
       prefetch(Tag<(KS + 1) & 7>{}, Tag<(VS + 1) & 7>{});   // K(t+2), V(t): first operands of step t+1
       PROF(3)
     }
-    // End of a pair (or step): everything but the requests of this pair (the last four steps) has
-    // landed, i.e. K up to t+5 and V up to t+3 seen from step t: what the steps up to the next
-    // barrier read, and what waves 4-7 prefetch before that barrier.  The barrier also separates
-    // the LDS reads before it from the requests after it into the same ring slots.
-    if constexpr (kPaired) {
-      if constexpr ((I & 1) == 1) {
-        wait_vm<4>();
-        PROF(4)
-        __syncthreads();
-      }
-    } else {
-#ifndef CALVO_SKIP_BARRIER
-      wait_vm<8>();
-      PROF(4)
-      __syncthreads();
-#endif
-    }
+    // End of the step: everything but the eight requests of the last four steps has landed,
+    // i.e. K up to t+3 and V up to t+1: what step t+1 reads, and what waves 4-7 prefetch at its
+    // end for step t+2.  The barrier also separates the LDS reads before it from the requests
+    // after it into the same ring slots.
+    wait_vm<8>();
+    PROF(4)
+    __syncthreads();
     PROF(5)
   };
 
@@ -620,16 +547,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #ifdef CALVO_PHASE_PROF
     prof_prev = (unsigned)clock64();
 #endif
-#ifdef CALVO_YOUNG_PRIO
-    if (wave >= 4) __builtin_amdgcn_s_setprio(CALVO_YOUNG_PRIO);
-#endif
-#if defined(CALVO_INPHASE)
-    if (true) {
-#elif defined(CALVO_SWAP_ROLES)
-    if (wave >= 4) {
-#else
     if (wave < 4) {
-#endif
       for (; t + 8 < n_pipe; t += 8) {
         fetch_next(t);
         step_steady(Tag<1>{}, Tag<0>{}, t);
@@ -658,11 +576,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       }
     }
   }
-#if defined(CALVO_PHASE_PROF) && CALVO_PHASE_PROF == 8
-  if (p.prof && blockIdx.x == 300)
-    for (int i = lane; i < 16 * 6; i += 64)
-      p.prof[wave * 96 + i] = *(long long*)(smem + kLdsBytes + (wave * 96 + i) * 8);
-#elif defined(CALVO_PHASE_PROF)
+#ifdef CALVO_PHASE_PROF
   if (lane == 0 && p.prof)
     p.prof[(long long)blockIdx.x * 8 + wave] = prof_acc;
 #endif
