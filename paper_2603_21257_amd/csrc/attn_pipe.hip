@@ -5,7 +5,7 @@
 //
 // Schedule.  The key loop advances in 32-key sub-tiles.  For sub-tile j the stages
 //     QK(j):  S_j = K_j Q^T                                     8 MFMA
-//     SM(j):  P_j = 2^(S_j - m), row sums                       ~55 vector-ALU instructions
+//     SM(j):  P_j = 2^(c (S_j - m)), row sums                   ~55 vector-ALU instructions
 //     PV(j):  O^T += V_j^T P_j^T                                8 MFMA
 // depend on each other, but QK(t+1), SM(t) and PV(t-1) do not.  Step t runs exactly these three:
 // the 16 MFMAs as one half of the step (QK_k and PV_k alternating, operands read from LDS four
@@ -13,8 +13,9 @@
 // steady loop is unrolled by eight so that register buffers and LDS ring slots are named
 // statically.
 //
-// Softmax.  Q is multiplied by scale * log2(e) and rounded to bf16 once, when it is loaded, so the
-// accumulators hold base-2 exponents and a weight is one subtract and one v_exp_f32.  In the
+// Softmax.  A weight is one fused multiply-add (score * scale * log2(e) - m * scale * log2(e))
+// and one v_exp_f32.  (Folding the factor into Q would save nothing - it replaces the multiply-add
+// by a subtract - and re-rounding Q costs accuracy when scores are large.)  In the
 // steady loop the reference m is raised lazily: the weights of a sub-tile are computed against
 // the current m, and only if a lane's partial row sum passes 2^16 is the sub-tile's maximum
 // taken, m raised, l and O rescaled and the weights computed again.  m is always the exact
@@ -186,9 +187,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
   const float c2 = p.scale * 1.4426950408889634f;
 
-  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8],
-  // multiplied by scale * log2(e) and rounded to bf16 again, so that the MFMA accumulators hold
-  // the scores in the base-2 exponent domain and the softmax needs no multiply per score
+  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8]
   bf16x8 qB[8];
   {
     const unsigned short* q = (const unsigned short*)p.q;
@@ -199,15 +198,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     for (int ks = 0; ks < 8; ks++) {
       u32x4 v = {0u, 0u, 0u, 0u};
       if (ok) v = *(const u32x4*)(row + 16 * ks);
-      u32x4 w;
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        bf16x2 pk;
-        pk[0] = (__bf16)(__builtin_bit_cast(float, v[j] << 16) * c2);
-        pk[1] = (__bf16)(__builtin_bit_cast(float, v[j] & 0xffff0000u) * c2);
-        w[j] = __builtin_bit_cast(unsigned, pk);
-      }
-      qB[ks] = __builtin_bit_cast(bf16x8, w);
+      qB[ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
@@ -216,10 +207,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   for (int dt = 0; dt < 4; dt++)
 #pragma unroll
     for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
-  // Softmax state per query (base-2 exponent domain): O and l_run are sums of weights
-  // 2^(score - m_run).  In the steady loop m_run is a reference that is only raised when a lane's
-  // partial row sum would pass kLazyBound; it is always the exact maximum of some earlier
-  // sub-tile, so the largest weight of a row is at least 1 and nothing underflows.
+  // Softmax state per query: O and l_run are sums of weights 2^(c2 (score - m_run)).  In the
+  // steady loop m_run is a reference that is only raised when a lane's partial row sum would
+  // pass kLazyBound; it is always the exact maximum of some earlier sub-tile, so the largest
+  // weight of a row is at least 1 and nothing underflows.
   float m_run = -INFINITY, l_run = 0.f;
 
   // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches rows 4(w&3)..+3 of block
@@ -305,16 +296,16 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
     mx = half_swap_max(mx);
     const float m_new = fmaxf(m_run, mx);
-    alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
     changed = (m_new != m_run);
     m_run = m_new;
-    mc = m_new;
+    mc = m_new * c2;
   };
   // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the rounded
   // values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
   auto sm_pair = [&](const f32x16& s, int e, float mc, float& ps) -> unsigned {
-    const float p0 = __builtin_amdgcn_exp2f(s[2 * e] - mc);
-    const float p1 = __builtin_amdgcn_exp2f(s[2 * e + 1] - mc);
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, -mc));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, -mc));
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
@@ -402,12 +393,13 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the
       // rounded values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
       auto weights = [&]() {
+        const float mc = m_run * c2;
         float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           bf16x2 w;
-          w[0] = (__bf16)__builtin_amdgcn_exp2f(s[2 * e] - m_run);
-          w[1] = (__bf16)__builtin_amdgcn_exp2f(s[2 * e + 1] - m_run);
+          w[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, -mc));
+          w[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, -mc));
           if (e & 1) ps1 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps1, false);
           else ps0 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps0, false);
           pk[e] = __builtin_bit_cast(unsigned, w);
@@ -426,7 +418,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #pragma unroll
         for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
         const float m_new = fmaxf(m_run, half_swap_max(mx));
-        a_acc = __builtin_amdgcn_exp2f(m_run - m_new);
+        a_acc = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
         changed = (m_new != m_run);
         m_run = m_new;
         l_run *= a_acc;

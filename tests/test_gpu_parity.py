@@ -38,6 +38,33 @@ def test_bf16_mfma_single_request(P, S):
     check(w)
 
 
+def _scale_prefix_keys(w, gain):
+    """Multiply the K rows of the cached prefix by gain(position) (re-rounded to bf16), in place."""
+    from oracle import calvo_oracle as orc
+    s = w.shape
+    B = s.block_tokens
+    for r in w.requests:
+        for j in range(r.n_prefix_blocks):
+            blk = w.host_kv[:, r.host_block_start + j].reshape(s.n_layers, 2, B, s.n_kv_heads * s.head_dim)
+            g = np.array([gain(j * B + i) for i in range(B)], np.float64)[None, :, None]
+            blk[:, 0] = wl.f32_to_bf16_bits((orc.widen(blk[:, 0]) * g).astype(np.float32))
+
+
+@pytest.mark.parametrize("pattern", ["growing", "spike", "shrinking"])
+def test_bf16_scores_that_outgrow_the_softmax_reference(pattern):
+    """The pipelined kernel keeps a softmax reference that it raises only when a weight gets too
+    large.  Keys whose scores grow along the sequence (or jump once) force that path in the
+    middle of the pipelined loop; keys that shrink leave an early large reference in place."""
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 192)
+    P, S = 2048, 96
+    w = wl.make_custom(shape, [(P, S)], seed=900 + len(pattern))
+    gain = {"growing": lambda pos: 1.0 + 60.0 * (pos / P) ** 2,
+            "spike": lambda pos: 80.0 if pos == 1037 else 1.0,
+            "shrinking": lambda pos: 60.0 * (1.0 - pos / P) ** 2 + 0.05}[pattern]
+    _scale_prefix_keys(w, gain)
+    check(w)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2), (6, 2), (12, 4)])
 def test_bf16_mfma_gqa_group_sizes(Hq, Hkv):
     shape = wl.Shape(1, Hq, Hkv, 128, "bf16", 64)
