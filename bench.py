@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # HBM bytes of one attention launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in
 # profiles/attn_pipe_kernel_cfg3.md (calibrated against the scatter kernel, a plain copy of known size).
 # Counters cannot be read from inside this process, so the figure is carried over from that profile.
-PROFILED_HBM_BYTES_PER_LAUNCH = {3: 645.3e6}
+PROFILED_HBM_BYTES_PER_LAUNCH = {3: 651.8e6}
 
 
 def log(*a):
