@@ -75,6 +75,26 @@ def test_ingest_layer_range_and_first_block():
             assert same == moved
 
 
+def test_ingest_of_a_batch_reads_each_request_from_its_own_host_blocks():
+    """Two requests staged back to back in one host area, the second sharing a run of slots with the
+    first: request r's block j comes from host block host_block_start_r + j, and shared blocks are
+    loaded once (first_ingest_block)."""
+    shape = wl.Shape(2, 2, 1, 8, "bf16", 32, block_tokens=4)
+    w = wl.make_custom(shape, [(20, 3), (28, 2)], seed=14, shared_blocks=2)
+    r0, r1 = w.requests
+    assert r0.host_block_start == 0 and r1.host_block_start > 0 and r1.first_ingest_block == 2
+    pool = np.full((2, 32, shape.blk_elems), 0xFFFF, np.uint16)
+    moved = sum(orc.kv_ingest(pool, w.host_kv, r.table, r.n_prefix_blocks, r.first_ingest_block, r.host_block_start)
+                for r in w.requests)
+    assert moved == w.ingest_bytes()
+    # independent statement: whole-array fancy indexing per request
+    for r in w.requests:
+        js = np.arange(r.first_ingest_block, r.n_prefix_blocks)
+        assert np.array_equal(pool[:, r.table[js]], w.host_kv[:, r.host_block_start + js])
+    assert np.array_equal(r0.table[:2], r1.table[:2])          # the shared run names the same slots
+    assert not np.array_equal(w.host_kv[:, 2], w.host_kv[:, r1.host_block_start + 2])   # distinct payloads per request
+
+
 def test_ingest_preserves_nan_payloads_and_negative_zero():
     shape = wl.Shape(1, 2, 1, 8, "f32", 8, block_tokens=4)
     w = wl.make_custom(shape, [(8, 1)], seed=9)
