@@ -103,6 +103,51 @@ int calvo_destroy(calvo_ctx* ctx);
  * blocks; CALVO_EHIP if HIP refuses a transfer (queued work so far still completes). */
 int calvo_kv_ingest(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end);
 
+/* Three-stage loading: remote store (L3) -> local host DRAM (L2) -> HBM (L1), each stage moving a
+ * block as soon as its source is ready and its destination is free, and signalling the stage above
+ * (paper Section 3.1; Section 4.1 gives the L3 link as 400 Gbps).  The remote store is emulated:
+ * the requests' host_kv may be ordinary pageable HOST memory; a loader thread owned by the context
+ * copies it chunk by chunk with n_threads host threads into a ring of n_slots pinned buffers (the
+ * bounded L2 staging area), never faster than l3_GBps, and hands every landed chunk to the L2 -> L1
+ * stage of calvo_kv_ingest (copy engine into the device staging ring, scatter into the pool).  A ring
+ * slot is reused once its host-to-device copy has finished.  Layer l's event is recorded after the
+ * last chunk of layer l. */
+typedef struct {
+  size_t  chunk_bytes; /* bytes per pinned ring slot, rounded down to whole blocks and to the device
+                          staging buffer size; 0 = the staging buffer size */
+  int32_t n_slots;     /* pinned ring slots, 2..8 (0 = 3) */
+  int32_t n_threads;   /* host threads of the L3 -> L2 copy, 1..32 (0 = 4) */
+  double  l3_GBps;     /* emulated link rate in 1e9 bytes/s: a chunk of n bytes occupies the link for
+                          at least n / rate; 0 = as fast as the host copies */
+} calvo_l3_config;
+
+typedef struct {
+  int64_t bytes;        /* bytes moved L3 -> L2 */
+  int32_t chunks;       /* ring slots filled */
+  double  l3_busy_s;    /* time the emulated link was occupied (copy + throttle) */
+  double  ring_wait_s;  /* time the loader waited for a free ring slot (L2 -> L1 slower than L3 -> L2) */
+  double  total_s;      /* from the call to the last chunk handed to the L2 -> L1 stage */
+} calvo_l3_stats;
+
+/* Same result in the pool as calvo_kv_ingest (raw bytes, bit exact, nothing else written), with the
+ * source in pageable host memory and the L3 -> L2 stage described above in front.  Returns after
+ * validation and after starting the loader thread; loading proceeds in the background.  The source
+ * memory must stay valid and unchanged until calvo_l3_wait (or the last layer's event).  While a
+ * loader runs, calvo_layer_event(QUERY) reports CALVO_ENOTREADY for layers not yet handed over,
+ * HOST_WAIT / STREAM_WAIT and calvo_prefill_attn block the calling thread until the layer's last
+ * chunk has been handed to the L2 -> L1 stage (the wait for L1 residency itself stays on the
+ * device), and a further calvo_kv_ingest / calvo_kv_ingest_l3 call first waits for the loader.
+ * Needs a context with staging buffers (staging_bytes > 0).  l3 == NULL selects all defaults.
+ * Errors (nothing started): as calvo_kv_ingest, plus CALVO_EINVAL for out-of-range l3 fields or a
+ * zero-copy context, CALVO_ENOMEM if the pinned ring cannot be allocated. */
+int calvo_kv_ingest_l3(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end,
+                       const calvo_l3_config* l3);
+
+/* Blocks until the loader started by calvo_kv_ingest_l3 has handed over its last chunk (or failed)
+ * and returns its status; stats (may be NULL) receives its counters.  CALVO_OK with zeroed stats if
+ * no loader was started.  Device-side completion is still observed through calvo_layer_event. */
+int calvo_l3_wait(calvo_ctx* ctx, calvo_l3_stats* stats);
+
 /* Per-layer "blocks are resident" signal (paper Section 3.1: a stage signals the stage above
  * when a block has been loaded).  mode:
  *   CALVO_EV_QUERY        CALVO_OK if layer's ingest has finished, else CALVO_ENOTREADY

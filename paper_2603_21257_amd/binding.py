@@ -21,8 +21,8 @@ CALVO_BF16, CALVO_F32 = 0, 1
 CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
-EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_layer_event", "calvo_prefill_attn",
-           "calvo_attn_kernel_ms", "calvo_last_error"]
+EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_l3", "calvo_l3_wait",
+           "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_last_error"]
 
 
 class calvo_config(C.Structure):
@@ -35,6 +35,15 @@ class calvo_config(C.Structure):
 class calvo_request(C.Structure):
     _fields_ = [("host_kv", C.c_void_p), ("host_layer_stride", C.c_int64), ("block_table", C.POINTER(C.c_int32)),
                 ("n_prefix_blocks", C.c_int32), ("first_ingest_block", C.c_int32), ("suffix_len", C.c_int32)]
+
+
+class calvo_l3_config(C.Structure):
+    _fields_ = [("chunk_bytes", C.c_size_t), ("n_slots", C.c_int32), ("n_threads", C.c_int32), ("l3_GBps", C.c_double)]
+
+
+class calvo_l3_stats(C.Structure):
+    _fields_ = [("bytes", C.c_int64), ("chunks", C.c_int32), ("l3_busy_s", C.c_double), ("ring_wait_s", C.c_double),
+                ("total_s", C.c_double)]
 
 
 class CalvoError(RuntimeError):
@@ -57,6 +66,9 @@ def lib() -> C.CDLL:
         L.calvo_create.argtypes = [C.POINTER(calvo_config), C.POINTER(C.c_void_p)]
         L.calvo_destroy.argtypes = [C.c_void_p]
         L.calvo_kv_ingest.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int]
+        L.calvo_kv_ingest_l3.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int,
+                                         C.POINTER(calvo_l3_config)]
+        L.calvo_l3_wait.argtypes = [C.c_void_p, C.POINTER(calvo_l3_stats)]
         L.calvo_layer_event.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
@@ -123,6 +135,19 @@ def calvo_destroy(ctx: int) -> None:
 
 def calvo_kv_ingest(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int) -> None:
     _check(lib().calvo_kv_ingest(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end))
+
+
+def calvo_kv_ingest_l3(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int,
+                       chunk_bytes: int = 0, n_slots: int = 0, n_threads: int = 0, l3_GBps: float = 0.0) -> None:
+    """host_kv of the requests may be pageable host memory; it must stay alive until calvo_l3_wait."""
+    cfg = calvo_l3_config(int(chunk_bytes), int(n_slots), int(n_threads), float(l3_GBps))
+    _check(lib().calvo_kv_ingest_l3(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end, C.byref(cfg)))
+
+
+def calvo_l3_wait(ctx: int) -> dict:
+    st = calvo_l3_stats()
+    _check(lib().calvo_l3_wait(ctx, C.byref(st)))
+    return {name: getattr(st, name) for name, _ in calvo_l3_stats._fields_}
 
 
 def calvo_layer_event(ctx: int, layer: int, mode: int, stream=None) -> bool:

@@ -1,13 +1,18 @@
 // Host side of libcalvo: argument validation, the ingest pipeline (paper Section 3.1,
-// the L2->L1 loading stage with its per-layer completion signal), the block-table cache
-// and the launch of the compute stage.  See include/calvo.h for the contract.
+// the L2->L1 loading stage with its per-layer completion signal, and the emulated L3->L2
+// stage in front of it), the block-table cache and the launch of the compute stage.
+// See include/calvo.h for the contract.
 #include <algorithm>
+#include <chrono>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/calvo.h"
@@ -74,6 +79,21 @@ struct calvo_ctx {
   std::vector<hipEvent_t> ev_t0, ev_t1;
   std::vector<char> timed;
   int scatter_grid = 64;
+  int device = 0;
+  // ---- emulated L3 -> L2 stage: a loader thread, a ring of pinned buffers, and the hand-over
+  // state it shares with the calling thread (layer_issued, l3_*: guarded by mu)
+  std::mutex mu;
+  std::condition_variable cv;
+  std::thread loader;
+  bool loader_started = false;
+  std::vector<char> layer_pending;           // layers a running loader will still hand over
+  int l3_status = CALVO_OK;
+  std::string l3_err;
+  calvo_l3_stats l3_stats{};
+  std::vector<void*> l2_ring;
+  std::vector<hipEvent_t> ev_l2_free;
+  std::vector<char> l2_free_recorded;
+  size_t l2_slot_bytes = 0;
 };
 
 namespace {
@@ -87,6 +107,9 @@ void destroy_partial(calvo_ctx* c) {
   for (auto e : c->ev_layer) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_t0) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_t1) if (e) (void)hipEventDestroy(e);
+  for (void* p : c->l2_ring)
+    if (p) (void)hipHostFree(p);
+  for (auto e : c->ev_l2_free) if (e) (void)hipEventDestroy(e);
   if (c->ev_tab_ing) (void)hipEventDestroy(c->ev_tab_ing);
   if (c->ev_att) (void)hipEventDestroy(c->ev_att);
   if (c->d_tab_ing) (void)hipFree(c->d_tab_ing);
@@ -191,6 +214,154 @@ int ensure_att_blob(calvo_ctx* c, size_t n) {
   return CALVO_OK;
 }
 
+
+// Waits for a running L3 loader and returns its status (CALVO_OK if none ran).
+int join_loader(calvo_ctx* c) {
+  if (c->loader_started) {
+    if (c->loader.joinable()) c->loader.join();
+    c->loader_started = false;
+  }
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->l3_status != CALVO_OK) g_err = c->l3_err;
+  return c->l3_status;
+}
+
+// Blocks until a running loader has handed `layer` to the L2->L1 stage (or failed).
+int wait_handed_over(calvo_ctx* c, int layer) {
+  std::unique_lock<std::mutex> lk(c->mu);
+  c->cv.wait(lk, [&] { return !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
+  if (c->layer_pending[layer]) {
+    g_err = c->l3_err;
+    return c->l3_status;
+  }
+  return CALVO_OK;
+}
+
+bool layer_is_issued(calvo_ctx* c, int layer) {
+  std::lock_guard<std::mutex> lk(c->mu);
+  return c->layer_issued[layer] != 0;
+}
+
+// L2->L1 for nb consecutive blocks (nb <= staging_blocks) that sit in page-locked host memory:
+// copy engine into the next device staging buffer, then scatter into the pool through the table.
+// If done is given it is recorded on the copy stream right after the transfer (the source may be
+// overwritten once it fires).
+hipError_t enqueue_staged(calvo_ctx* c, const unsigned char* pinned_src, unsigned char* pool_layer,
+                          const int32_t* d_table, int64_t nb, hipEvent_t done) {
+  const int b = (int)(c->seq % (uint64_t)c->n_staging);
+  hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
+  hipError_t e;
+  if (c->free_recorded[b] && (e = hipStreamWaitEvent(cs, c->ev_free[b], 0)) != hipSuccess) return e;
+  if ((e = hipMemcpyAsync(c->staging[b], pinned_src, (size_t)nb * c->blk_bytes, hipMemcpyHostToDevice, cs)) != hipSuccess) return e;
+  if (done && (e = hipEventRecord(done, cs)) != hipSuccess) return e;
+  if ((e = hipEventRecord(c->ev_filled[b], cs)) != hipSuccess) return e;
+  if ((e = hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0)) != hipSuccess) return e;
+  if ((e = launch_scatter_blocks(c->staging[b], pool_layer, d_table, nb, (int32_t)c->blk_bytes, 1024, c->s_scatter)) != hipSuccess) return e;
+  if ((e = hipEventRecord(c->ev_free[b], c->s_scatter)) != hipSuccess) return e;
+  c->free_recorded[b] = 1;
+  c->seq++;
+  return hipSuccess;
+}
+
+struct L3Request {            // what the loader keeps of a calvo_request after the call has returned
+  const unsigned char* src;   // pageable "remote" memory
+  int64_t layer_stride;
+  int64_t first, nblk;
+  size_t tab_off;
+};
+
+struct L3Job {
+  std::vector<L3Request> reqs;
+  int layer_begin = 0, layer_end = 0;
+  int64_t chunk_blocks = 0;
+  int n_slots = 0, n_threads = 0;
+  double rate = 0.0;          // bytes per second, 0 = unthrottled
+};
+
+void parallel_copy(unsigned char* dst, const unsigned char* src, size_t n, int n_threads) {
+  size_t piece = (n / (size_t)n_threads + 4095) & ~(size_t)4095;
+  if (piece == 0 || n_threads <= 1 || n <= piece) {
+    memcpy(dst, src, n);
+    return;
+  }
+  std::vector<std::thread> th;
+  for (size_t off = piece; off < n; off += piece)
+    th.emplace_back([=] { memcpy(dst + off, src + off, std::min(piece, n - off)); });
+  memcpy(dst, src, piece);
+  for (auto& t : th) t.join();
+}
+
+// Body of the loader thread: L3 -> L2 (host copy into the pinned ring, rate limited), then the
+// hand-over of every landed chunk to the L2 -> L1 stage.
+void loader_main(calvo_ctx* c, L3Job job) {
+  using clock = std::chrono::steady_clock;
+  const auto t_begin = clock::now();
+  calvo_l3_stats st{};
+  int status = CALVO_OK;
+  std::string err;
+  auto hip_fail = [&](hipError_t e, const char* what) {
+    (void)hipGetLastError();
+    status = e == hipErrorOutOfMemory ? CALVO_ENOMEM : CALVO_EHIP;
+    err = std::string(what) + ": " + hipGetErrorString(e);
+  };
+  hipError_t e = hipSetDevice(c->device);
+  if (e != hipSuccess) hip_fail(e, "hipSetDevice (loader)");
+  auto link_free_at = clock::now();          // when the emulated link can start its next chunk
+  uint64_t k = 0;
+  for (int l = job.layer_begin; l < job.layer_end && status == CALVO_OK; l++) {
+    unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
+    for (size_t r = 0; r < job.reqs.size() && status == CALVO_OK; r++) {
+      const L3Request& q = job.reqs[r];
+      for (int64_t j0 = q.first; j0 < q.nblk && status == CALVO_OK; j0 += job.chunk_blocks, k++) {
+        const int64_t nb = std::min<int64_t>(job.chunk_blocks, q.nblk - j0);
+        const size_t bytes = (size_t)nb * c->blk_bytes;
+        const int slot = (int)(k % (uint64_t)job.n_slots);
+        auto t0 = clock::now();
+        if (c->l2_free_recorded[slot] && (e = hipEventSynchronize(c->ev_l2_free[slot])) != hipSuccess) {
+          hip_fail(e, "hipEventSynchronize (L2 ring slot)");
+          break;
+        }
+        auto t1 = clock::now();
+        const double waited = std::chrono::duration<double>(t1 - t0).count();
+        st.ring_wait_s += waited;
+        // The emulated link streams on its own: the time this thread spends handing a chunk to the
+        // next stage does not hold it up.  It starts the next chunk when it is free, unless it had
+        // to wait for a ring slot (back-pressure from L2 -> L1), in which case it starts now.
+        const auto start = waited > 50e-6 ? std::max(t1, link_free_at) : link_free_at;
+        parallel_copy((unsigned char*)c->l2_ring[slot],
+                      q.src + (int64_t)l * q.layer_stride + j0 * (int64_t)c->blk_bytes, bytes, job.n_threads);
+        if (job.rate > 0.0) {
+          link_free_at = start + std::chrono::duration_cast<clock::duration>(std::chrono::duration<double>((double)bytes / job.rate));
+          std::this_thread::sleep_until(link_free_at);
+        }
+        st.l3_busy_s += std::chrono::duration<double>(clock::now() - t1).count();
+        st.bytes += (int64_t)bytes;
+        st.chunks++;
+        e = enqueue_staged(c, (const unsigned char*)c->l2_ring[slot], pool_layer, c->d_tab_ing + q.tab_off + j0, nb,
+                           c->ev_l2_free[slot]);
+        if (e != hipSuccess) { hip_fail(e, "L2 -> L1 hand-over"); break; }
+        c->l2_free_recorded[slot] = 1;
+      }
+    }
+    if (status != CALVO_OK) break;
+    if ((e = hipEventRecord(c->ev_layer[l], c->s_scatter)) != hipSuccess) { hip_fail(e, "hipEventRecord (layer)"); break; }
+    {
+      std::lock_guard<std::mutex> lk(c->mu);
+      c->layer_issued[l] = 1;
+      c->layer_pending[l] = 0;
+    }
+    c->cv.notify_all();
+  }
+  st.total_s = std::chrono::duration<double>(clock::now() - t_begin).count();
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->l3_stats = st;
+    c->l3_status = status;
+    c->l3_err = err;
+  }
+  c->cv.notify_all();     // on failure the waiters see the status; pending layers stay pending
+}
+
 }  // namespace
 
 extern "C" {
@@ -207,6 +378,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   calvo_ctx* c = new (std::nothrow) calvo_ctx();
   if (!c) return fail(CALVO_ENOMEM, "out of host memory");
   c->cfg = *cfg;
+  c->device = dev;
   c->elt = cfg->dtype == CALVO_BF16 ? 2 : 4;
   c->blk_bytes = (size_t)2 * kBlockTokens * cfg->n_kv_heads * cfg->head_dim * c->elt;
   c->layer_bytes = (int64_t)cfg->pool_blocks * (int64_t)c->blk_bytes;
@@ -245,6 +417,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->ev_t0.assign(cfg->n_layers, nullptr);
   c->ev_t1.assign(cfg->n_layers, nullptr);
   c->layer_issued.assign(cfg->n_layers, 0);
+  c->layer_pending.assign(cfg->n_layers, 0);
   c->timed.assign(cfg->n_layers, 0);
   for (int l = 0; l < cfg->n_layers; l++) {
     CREATE_TRY(hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming));
@@ -260,6 +433,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
 
 int calvo_destroy(calvo_ctx* c) {
   if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  (void)join_loader(c);
   hipError_t e = hipSuccess, t;
   for (auto& s : c->s_copy)
     if (s && (t = hipStreamSynchronize(s)) != hipSuccess) e = t;
@@ -270,41 +444,47 @@ int calvo_destroy(calvo_ctx* c) {
   return CALVO_OK;
 }
 
-int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end) {
-  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+}  // extern "C"
+
+namespace {
+
+// Front part shared by both ingest calls: validation, source pointers, block tables to the device.
+// pinned: the sources must be page-locked (and device-mapped for the zero-copy mode).
+int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end, bool pinned,
+                   std::vector<const unsigned char*>& src, std::vector<size_t>& tab_off) {
   if (layer_begin < 0 || layer_end > c->cfg.n_layers || layer_begin > layer_end)
     return fail(CALVO_EINVAL, "layer range [%d, %d) outside [0, %d]", layer_begin, layer_end, c->cfg.n_layers);
   std::vector<char> seen;
   int rc = validate_requests(c, reqs, n_reqs, true, seen);
   if (rc != CALVO_OK) return rc;
-
-  // the source must be page-locked host memory the device can address
-  std::vector<const unsigned char*> src(n_reqs, nullptr);
-  std::vector<size_t> tab_off(n_reqs, 0);
+  src.assign(n_reqs, nullptr);
+  tab_off.assign(n_reqs, 0);
   size_t n_tab = 0;
   for (int r = 0; r < n_reqs; r++) {
     tab_off[r] = n_tab;
     n_tab += (size_t)reqs[r].n_prefix_blocks;
     if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) continue;
-    hipPointerAttribute_t attr;
-    hipError_t e = hipPointerGetAttributes(&attr, reqs[r].host_kv);
-    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
-      (void)hipGetLastError();
-      return fail(CALVO_EINVAL, "request %d: host_kv is not page-locked host memory", r);
-    }
     void* dp = const_cast<void*>(reqs[r].host_kv);
-    if (c->n_staging == 0) {
-      dp = nullptr;
-      e = hipHostGetDevicePointer(&dp, const_cast<void*>(reqs[r].host_kv), 0);
-      if (e != hipSuccess || !dp) {
+    if (pinned) {
+      // the source must be page-locked host memory the device can address
+      hipPointerAttribute_t attr;
+      hipError_t e = hipPointerGetAttributes(&attr, reqs[r].host_kv);
+      if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
         (void)hipGetLastError();
-        return fail(CALVO_EINVAL, "request %d: host_kv has no device mapping", r);
+        return fail(CALVO_EINVAL, "request %d: host_kv is not page-locked host memory", r);
+      }
+      if (c->n_staging == 0) {
+        dp = nullptr;
+        e = hipHostGetDevicePointer(&dp, const_cast<void*>(reqs[r].host_kv), 0);
+        if (e != hipSuccess || !dp) {
+          (void)hipGetLastError();
+          return fail(CALVO_EINVAL, "request %d: host_kv has no device mapping", r);
+        }
       }
     }
     src[r] = (const unsigned char*)dp;
   }
   if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
-
   // block tables -> device (ingest stream)
   if (n_tab > 0) {
     rc = ensure_ing_table(c, n_tab);
@@ -317,6 +497,22 @@ int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int lay
     HIP_TRY(hipEventRecord(c->ev_tab_ing, c->s_scatter));
     c->tab_ing_pending = true;
   }
+  return CALVO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  int rc = join_loader(c);
+  if (rc != CALVO_OK) return rc;
+  std::vector<const unsigned char*> src;
+  std::vector<size_t> tab_off;
+  rc = prepare_ingest(c, reqs, n_reqs, layer_begin, layer_end, true, src, tab_off);
+  if (rc != CALVO_OK) return rc;
+  if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
 
   for (int l = layer_begin; l < layer_end; l++) {
     unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
@@ -333,25 +529,95 @@ int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int lay
       } else {
         for (int64_t j0 = first; j0 < nblk; j0 += c->staging_blocks) {
           const int64_t nb = std::min<int64_t>(c->staging_blocks, nblk - j0);
-          const int b = (int)(c->seq % (uint64_t)c->n_staging);
-          hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
-          if (c->free_recorded[b]) HIP_TRY(hipStreamWaitEvent(cs, c->ev_free[b], 0));
-          HIP_TRY(hipMemcpyAsync(c->staging[b], lsrc + j0 * (int64_t)c->blk_bytes, (size_t)nb * c->blk_bytes,
-                                 hipMemcpyHostToDevice, cs));
-          HIP_TRY(hipEventRecord(c->ev_filled[b], cs));
-          HIP_TRY(hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0));
-          HIP_TRY(launch_scatter_blocks(c->staging[b], pool_layer, c->d_tab_ing + tab_off[r] + j0, nb,
-                                        (int32_t)c->blk_bytes, 1024, c->s_scatter));
-          HIP_TRY(hipEventRecord(c->ev_free[b], c->s_scatter));
-          c->free_recorded[b] = 1;
-          c->seq++;
+          HIP_TRY(enqueue_staged(c, lsrc + j0 * (int64_t)c->blk_bytes, pool_layer, c->d_tab_ing + tab_off[r] + j0, nb,
+                                 nullptr));
         }
       }
     }
     HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
+    std::lock_guard<std::mutex> lk(c->mu);
     c->layer_issued[l] = 1;
   }
   return CALVO_OK;
+}
+
+int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end,
+                       const calvo_l3_config* l3) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (c->n_staging == 0) return fail(CALVO_EINVAL, "three-stage loading needs a context with staging buffers");
+  calvo_l3_config cfg{};
+  if (l3) cfg = *l3;
+  if (cfg.n_slots != 0 && (cfg.n_slots < 2 || cfg.n_slots > 8)) return fail(CALVO_EINVAL, "l3: n_slots must be 0 or in [2, 8]");
+  if (cfg.n_threads < 0 || cfg.n_threads > 32) return fail(CALVO_EINVAL, "l3: n_threads must be in [0, 32]");
+  if (!(cfg.l3_GBps >= 0.0)) return fail(CALVO_EINVAL, "l3: l3_GBps must be non-negative");
+  if (cfg.chunk_bytes != 0 && cfg.chunk_bytes < c->blk_bytes)
+    return fail(CALVO_EINVAL, "l3: chunk_bytes (%zu) is smaller than one block (%zu)", cfg.chunk_bytes, c->blk_bytes);
+  int rc = join_loader(c);
+  if (rc != CALVO_OK) return rc;
+  std::vector<const unsigned char*> src;
+  std::vector<size_t> tab_off;
+  rc = prepare_ingest(c, reqs, n_reqs, layer_begin, layer_end, false, src, tab_off);
+  if (rc != CALVO_OK) return rc;
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->l3_stats = calvo_l3_stats{};
+  }
+  if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
+
+  L3Job job;
+  job.layer_begin = layer_begin;
+  job.layer_end = layer_end;
+  job.n_slots = cfg.n_slots ? cfg.n_slots : 3;
+  job.n_threads = cfg.n_threads ? cfg.n_threads : 4;
+  job.rate = cfg.l3_GBps * 1e9;
+  const int64_t want = cfg.chunk_bytes ? (int64_t)(cfg.chunk_bytes / c->blk_bytes) : c->staging_blocks;
+  job.chunk_blocks = std::min<int64_t>(want, c->staging_blocks);
+  for (int r = 0; r < n_reqs; r++)
+    if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block)
+      job.reqs.push_back({src[r], reqs[r].host_layer_stride, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks, tab_off[r]});
+
+  // the pinned ring (kept for later calls; regrown if a call asks for more)
+  const size_t slot_bytes = (size_t)job.chunk_blocks * c->blk_bytes;
+  if (slot_bytes > c->l2_slot_bytes || (int)c->l2_ring.size() < job.n_slots) {
+    for (auto& s : c->s_copy) if (s) HIP_TRY(hipStreamSynchronize(s));
+    for (void* p : c->l2_ring) if (p) (void)hipHostFree(p);
+    for (auto e : c->ev_l2_free) if (e) (void)hipEventDestroy(e);
+    c->l2_ring.assign(job.n_slots, nullptr);
+    c->ev_l2_free.assign(job.n_slots, nullptr);
+    c->l2_free_recorded.assign(job.n_slots, 0);
+    c->l2_slot_bytes = 0;
+    for (int i = 0; i < job.n_slots; i++) {
+      hipError_t e = hipHostMalloc(&c->l2_ring[i], slot_bytes, hipHostMallocDefault);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_l2_free[i], hipEventDisableTiming);
+      if (e != hipSuccess) return fail_hip(e, "pinned L2 ring");
+    }
+    c->l2_slot_bytes = slot_bytes;
+  }
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    for (int l = layer_begin; l < layer_end; l++) { c->layer_pending[l] = 1; c->layer_issued[l] = 0; }
+    c->l3_status = CALVO_OK;
+    c->l3_err.clear();
+  }
+  try {
+    c->loader = std::thread(loader_main, c, std::move(job));
+  } catch (...) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    for (int l = layer_begin; l < layer_end; l++) c->layer_pending[l] = 0;
+    return fail(CALVO_ENOMEM, "cannot start the loader thread");
+  }
+  c->loader_started = true;
+  return CALVO_OK;
+}
+
+int calvo_l3_wait(calvo_ctx* c, calvo_l3_stats* stats) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  const int rc = join_loader(c);
+  if (stats) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    *stats = c->l3_stats;
+  }
+  return rc;
 }
 
 int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
@@ -359,7 +625,17 @@ int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
   if (mode != CALVO_EV_QUERY && mode != CALVO_EV_HOST_WAIT && mode != CALVO_EV_STREAM_WAIT)
     return fail(CALVO_EINVAL, "unknown mode %d", mode);
-  if (!c->layer_issued[layer]) return CALVO_OK;
+  if (mode == CALVO_EV_QUERY) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->layer_pending[layer]) {
+      if (c->l3_status != CALVO_OK) { g_err = c->l3_err; return c->l3_status; }
+      return fail(CALVO_ENOTREADY, "layer %d is still loading", layer);
+    }
+  } else {
+    const int rc = wait_handed_over(c, layer);
+    if (rc != CALVO_OK) return rc;
+  }
+  if (!layer_is_issued(c, layer)) return CALVO_OK;
   if (mode == CALVO_EV_QUERY) {
     hipError_t e = hipEventQuery(c->ev_layer[layer]);
     if (e == hipSuccess) return CALVO_OK;
@@ -397,7 +673,9 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   if (total == 0) {
     // nothing to compute; still order the compute stream after the layer's ingest
-    if (c->layer_issued[layer]) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+    rc = wait_handed_over(c, layer);
+    if (rc != CALVO_OK) return rc;
+    if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
     return CALVO_OK;
   }
 
@@ -473,7 +751,9 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     c->att_pending = true;
   }
 
-  if (c->layer_issued[layer]) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+  rc = wait_handed_over(c, layer);          // a running L3 loader: until the layer's last chunk is queued
+  if (rc != CALVO_OK) return rc;
+  if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
 
   unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
   const ReqDesc* d_reqs = (const ReqDesc*)c->d_att;

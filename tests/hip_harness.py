@@ -107,6 +107,14 @@ def run_oracle(w: wl.Workload, scale=None, attn=True):
     return pool, out
 
 
+def sentinel_pool_after_ingest(w: wl.Workload) -> np.ndarray:
+    """Expected pool image after the ingest of all layers alone (no suffix append): oracle only."""
+    pool = sentinel_pool_np(w.shape)
+    for r in w.requests:
+        orc.kv_ingest(pool, w.host_kv, r.table, r.n_prefix_blocks, r.first_ingest_block, r.host_block_start)
+    return pool
+
+
 def assert_pool_bit_exact(got: np.ndarray, want: np.ndarray):
     g = got.view(np.uint16 if got.dtype == np.uint16 else np.uint32)
     e = want.view(np.uint16 if want.dtype == np.uint16 else np.uint32)

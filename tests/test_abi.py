@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "calvo.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(calvo_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(calvo_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -35,6 +35,10 @@ def test_struct_layouts_match_header_order():
         "host_kv", "host_layer_stride", "block_table", "n_prefix_blocks", "first_ingest_block", "suffix_len"]
     assert ctypes.sizeof(cb.calvo_config) == 64
     assert ctypes.sizeof(cb.calvo_request) == 40
+    assert [f[0] for f in cb.calvo_l3_config._fields_] == ["chunk_bytes", "n_slots", "n_threads", "l3_GBps"]
+    assert [f[0] for f in cb.calvo_l3_stats._fields_] == ["bytes", "chunks", "l3_busy_s", "ring_wait_s", "total_s"]
+    assert ctypes.sizeof(cb.calvo_l3_config) == 24
+    assert ctypes.sizeof(cb.calvo_l3_stats) == 40
 
 
 @pytest.mark.parametrize("kw,frag", [
@@ -62,6 +66,8 @@ def test_null_context_is_an_error_not_a_crash():
     lib = cb.lib()
     assert lib.calvo_destroy(None) == cb.CALVO_EINVAL
     assert lib.calvo_kv_ingest(None, None, 0, 0, 0) == cb.CALVO_EINVAL
+    assert lib.calvo_kv_ingest_l3(None, None, 0, 0, 0, None) == cb.CALVO_EINVAL
+    assert lib.calvo_l3_wait(None, None) == cb.CALVO_EINVAL
     assert lib.calvo_layer_event(None, 0, 0, None) == cb.CALVO_EINVAL
     assert lib.calvo_prefill_attn(None, 0, None, None, None, None, None, 0, None, ctypes.c_float(0)) == cb.CALVO_EINVAL
     assert "NULL" in cb.calvo_last_error()
