@@ -174,6 +174,57 @@ int calvo_layer_event(calvo_ctx* ctx, int layer, int mode, void* stream);
 int calvo_prefill_attn(calvo_ctx* ctx, int layer, const void* q, const void* k_suffix, const void* v_suffix,
                        void* out, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale);
 
+/* ---- Inter-request scheduling (paper Section 3.2; compared policies: Section 4.3).  Host code only.
+ *
+ * Cost model: "a binary linear function" fitted by offline profiling - loading latency linear in the
+ * number of context tokens to load, computation latency linear in the number of query tokens:
+ *     T_load = load_per_token_s * ctx_tokens + load_fixed_s      (0 when ctx_tokens == 0)
+ *     T_comp = comp_per_token_s * query_tokens + comp_fixed_s    (0 when query_tokens == 0)
+ * Policies order the queue by a priority, smaller first; ties go to the earlier arrival, then to the
+ * lower index:
+ *     CALVO_POLICY_FIFO    arrival time
+ *     CALVO_POLICY_SJF     T_load + T_comp of the model                 (optimises average TTFT)
+ *     CALVO_POLICY_SJF_PT  query_tokens, the number of tokens to prefill (the paper's SJF-PT)
+ *     CALVO_POLICY_LSTF    slack LST = deadline - T_load - T_comp        (optimises SLO attainment)
+ *     CALVO_POLICY_EDF     deadline
+ * Service is non-preemptive. */
+typedef struct {
+  double load_per_token_s, load_fixed_s, comp_per_token_s, comp_fixed_s;
+} calvo_cost_model;
+
+typedef struct {
+  double  arrival_s;    /* submission time */
+  double  deadline_s;   /* absolute TTFT deadline (LSTF, EDF); ignored by the other policies */
+  int64_t ctx_tokens;   /* context tokens whose KVCache must be loaded */
+  int64_t query_tokens; /* tokens that must be computed */
+} calvo_job;
+
+enum { CALVO_POLICY_FIFO = 0, CALVO_POLICY_SJF = 1, CALVO_POLICY_SJF_PT = 2, CALVO_POLICY_LSTF = 3, CALVO_POLICY_EDF = 4 };
+
+/* Least-squares line seconds = per_token_s * tokens + fixed_s through n >= 2 profiled samples (one
+ * call for the loading component, one for the computation component).  CALVO_EINVAL for NULLs,
+ * n < 2 or samples that all have the same token count. */
+int calvo_cost_fit(const double* tokens, const double* seconds, int n, double* per_token_s, double* fixed_s);
+
+/* T_load and T_comp of one job under the model. */
+int calvo_cost_estimate(const calvo_cost_model* model, const calvo_job* job, double* load_s, double* comp_s);
+
+/* The job to serve next at time `now`: among the jobs with done[i] == 0 (done may be NULL) and
+ * arrival_s <= now, the one with the smallest priority; *out_index = -1 if none has arrived.
+ * model may be NULL for policies that do not use it. */
+int calvo_sched_pick(int policy, const calvo_cost_model* model, const calvo_job* jobs, const unsigned char* done, int n,
+                     double now, int* out_index);
+
+/* Replays a whole trace on one server.  load_s / comp_s: the time each job's loading and computation
+ * actually take (HOST arrays of n; NULL = the model's estimates).  pipelined == 0: one job at a time,
+ * load then compute.  pipelined != 0: loading and computation are separate stages (Section 3.1), a
+ * job is taken when the loading stage is free and computes when its load has finished and the compute
+ * stage is free.  Whenever the (loading) stage is free and a job has arrived, the policy picks; if
+ * none has arrived the server idles until the next arrival.  Outputs: start_s[i] (loading starts) and
+ * finish_s[i] (first token; TTFT_i = finish_s[i] - arrival_s). */
+int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_job* jobs, int n, const double* load_s,
+                         const double* comp_s, int pipelined, double* start_s, double* finish_s);
+
 /* Measurement helper: duration in milliseconds of the most recent attention kernel queued by
  * calvo_prefill_attn for `layer` (HIP events recorded around the kernel on the compute
  * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */

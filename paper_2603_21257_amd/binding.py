@@ -22,7 +22,9 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_l3", "calvo_l3_wait",
-           "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_last_error"]
+           "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_sched_pick", "calvo_sched_simulate", "calvo_last_error"]
+CALVO_POLICY_FIFO, CALVO_POLICY_SJF, CALVO_POLICY_SJF_PT, CALVO_POLICY_LSTF, CALVO_POLICY_EDF = range(5)
 
 
 class calvo_config(C.Structure):
@@ -44,6 +46,16 @@ class calvo_l3_config(C.Structure):
 class calvo_l3_stats(C.Structure):
     _fields_ = [("bytes", C.c_int64), ("chunks", C.c_int32), ("l3_busy_s", C.c_double), ("ring_wait_s", C.c_double),
                 ("total_s", C.c_double)]
+
+
+class calvo_cost_model(C.Structure):
+    _fields_ = [("load_per_token_s", C.c_double), ("load_fixed_s", C.c_double), ("comp_per_token_s", C.c_double),
+                ("comp_fixed_s", C.c_double)]
+
+
+class calvo_job(C.Structure):
+    _fields_ = [("arrival_s", C.c_double), ("deadline_s", C.c_double), ("ctx_tokens", C.c_int64),
+                ("query_tokens", C.c_int64)]
 
 
 class CalvoError(RuntimeError):
@@ -73,6 +85,13 @@ def lib() -> C.CDLL:
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
+        dp = C.POINTER(C.c_double)
+        L.calvo_cost_fit.argtypes = [dp, dp, C.c_int, dp, dp]
+        L.calvo_cost_estimate.argtypes = [C.POINTER(calvo_cost_model), C.POINTER(calvo_job), dp, dp]
+        L.calvo_sched_pick.argtypes = [C.c_int, C.POINTER(calvo_cost_model), C.POINTER(calvo_job), C.POINTER(C.c_ubyte),
+                                       C.c_int, C.c_double, C.POINTER(C.c_int)]
+        L.calvo_sched_simulate.argtypes = [C.c_int, C.POINTER(calvo_cost_model), C.POINTER(calvo_job), C.c_int, dp, dp,
+                                           C.c_int, dp, dp]
         L.calvo_last_error.argtypes = []
         L.calvo_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -162,6 +181,63 @@ def calvo_prefill_attn(ctx: int, layer: int, q, k_suffix, v_suffix, out, reqs: S
     _check(lib().calvo_prefill_attn(ctx, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out),
                                     _req_array(reqs), len(reqs), cu.ctypes.data_as(C.POINTER(C.c_int32)),
                                     float(scale)))
+
+
+def _darr(x):
+    a = np.ascontiguousarray(x, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def _job_array(jobs):
+    """jobs: sequence of (arrival_s, deadline_s, ctx_tokens, query_tokens)."""
+    arr = (calvo_job * max(len(jobs), 1))()
+    for i, (a, d, c, q) in enumerate(jobs):
+        arr[i] = calvo_job(float(a), float(d), int(c), int(q))
+    return arr
+
+
+def _sched_check(rc: int):
+    if rc != CALVO_OK:
+        raise CalvoError(rc, "invalid scheduling argument")
+
+
+def calvo_cost_fit(tokens, seconds):
+    """Returns (per_token_s, fixed_s)."""
+    t, tp = _darr(tokens)
+    y, yp = _darr(seconds)
+    a, b = C.c_double(), C.c_double()
+    _sched_check(lib().calvo_cost_fit(tp, yp, min(len(t), len(y)), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def calvo_cost_estimate(model, job):
+    m = calvo_cost_model(*model)
+    j = calvo_job(float(job[0]), float(job[1]), int(job[2]), int(job[3]))
+    a, b = C.c_double(), C.c_double()
+    _sched_check(lib().calvo_cost_estimate(C.byref(m), C.byref(j), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def calvo_sched_pick(policy: int, model, jobs, done, now: float) -> int:
+    m = calvo_cost_model(*model) if model is not None else None
+    d = (C.c_ubyte * max(len(jobs), 1))(*[1 if x else 0 for x in done]) if done is not None else None
+    out = C.c_int(-2)
+    _sched_check(lib().calvo_sched_pick(policy, C.byref(m) if m is not None else None, _job_array(jobs), d, len(jobs),
+                                        float(now), C.byref(out)))
+    return out.value
+
+
+def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pipelined: bool = False):
+    """Returns (start_s, finish_s) as numpy arrays."""
+    m = calvo_cost_model(*model) if model is not None else None
+    n = len(jobs)
+    start, sp = _darr(np.zeros(max(n, 1)))
+    fin, fp = _darr(np.zeros(max(n, 1)))
+    la = _darr(load_s) if load_s is not None else (None, None)
+    ca = _darr(comp_s) if comp_s is not None else (None, None)
+    _sched_check(lib().calvo_sched_simulate(policy, C.byref(m) if m is not None else None, _job_array(jobs), n, la[1], ca[1],
+                                            1 if pipelined else 0, sp, fp))
+    return start[:n], fin[:n]
 
 
 def calvo_attn_kernel_ms(ctx: int, layer: int) -> float:

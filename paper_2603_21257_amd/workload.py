@@ -276,8 +276,9 @@ def make_config(cfg: int, seed: int = BASE_SEED, n_layers: Optional[int] = None,
     return _finish(CONFIG_NAMES[cfg], shape, reqs, seed, with_payload)
 
 
-def make_custom(shape: Shape, lengths, seed: int, shared_blocks: int = 0) -> Workload:
-    """Small test workload: lengths is a list of (prefix_len, suffix_len).
+def make_custom(shape: Shape, lengths, seed: int, shared_blocks: int = 0, with_payload: bool = True) -> Workload:
+    """Test workload: lengths is a list of (prefix_len, suffix_len).  with_payload=False leaves the
+    value arrays out (large cases fill caller-allocated buffers with fill_normal_).
 
     shared_blocks > 0 makes every request's first shared_blocks table entries the
     same slots (ingested by request 0 only), as in the varlen batch recipe.
@@ -297,4 +298,4 @@ def make_custom(shape: Shape, lengths, seed: int, shared_blocks: int = 0) -> Wor
         first = 0 if r == 0 else shared_blocks
         reqs.append(Request(p, s, table, first, host_cur - first, B))
         host_cur += p // B - first
-    return _finish("custom", shape, reqs, seed, True)
+    return _finish("custom", shape, reqs, seed, with_payload)
