@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--n-staging", type=int, default=0)
     ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--custom", type=str, default="",
+                    help="replace the workload's requests by 'P:S[,P:S...]' (prefix:suffix tokens) on the same model shape, "
+                         "e.g. 32768:64 for a long-context short-query point; the JSON line then describes that workload")
     ap.add_argument("--no-three-stage", action="store_true",
                     help="skip the extra measurement with the emulated remote store in front (L3 -> L2 -> L1 -> compute)")
     ap.add_argument("--l3-gbps", type=float, default=50.0, help="emulated L3 link rate (paper Section 4.1: 400 Gbps)")
@@ -70,6 +73,13 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     w = wl.make_config(args.config, with_payload=False)
+    if args.custom:
+        lens = [tuple(int(x) for x in item.split(":")) for item in args.custom.split(",")]
+        need = sum(-(-(p + q) // 16) for p, q in lens)
+        base = w.shape
+        shape = wl.Shape(base.n_layers, base.n_q_heads, base.n_kv_heads, base.head_dim, base.dtype, need + 16)
+        w = wl.make_custom(shape, lens, seed=w.seed, with_payload=False)
+        w.name = f"custom {args.custom} on the shape of cfg{args.config}"
     s = w.shape
     tdt = torch.bfloat16 if s.dtype == "bf16" else torch.float32
     L, T = s.n_layers, w.total_suffix

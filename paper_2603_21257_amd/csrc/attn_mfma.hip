@@ -340,6 +340,8 @@ static int attn_variant() {
   return v;
 }
 
+bool attn_mfma_splits_context() { return attn_variant() == 3; }
+
 int attn_mfma_tile_tokens(int heads_per_wg) {
   const int v = attn_variant();
   if (v == 3) return attn_pipe_tile_tokens(heads_per_wg);

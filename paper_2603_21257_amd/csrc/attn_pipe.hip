@@ -54,6 +54,7 @@ namespace pipe {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -173,8 +174,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   const int pq_max = P + min(wq0 + 32, S) - 1;
   const int ctx_len = P + S;
   const int n_keys = P + min(q_base + TQ, S);
-  const int n_sub = (n_keys + kSK - 1) / kSK;                 // sub-tiles this workgroup visits
-  const int n_pipe = min(n_sub, (P + q_base + 1) / kSK);      // ... fully visible to all its rows
+  // This work item covers the sub-tiles [jb, je) of the tile's context; t and j below count from jb.
+  const int jb = wi.sub_begin;
+  const int n_sub = wi.sub_end - jb;                           // sub-tiles this workgroup visits
+  const int n_pipe = max(0, min(wi.sub_end, (P + q_base + 1) / kSK) - jb);   // ... fully visible to all its rows
   const int last_blk = (ctx_len + kBlockTokens - 1) / kBlockTokens - 1;
   // the block table is read-only for the whole launch: reading it through the constant address
   // space keeps the lookups on the scalar unit, outside the vmcnt accounting of the K/V requests
@@ -226,7 +229,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   const unsigned dma_lds = lds0 + wave * 1024;                         // + slot*8192 (+ V ring)
 
   // byte offset of this wave's block of sub-tile j (the table is padded, so j may run past the end)
-  auto fetch_off = [&](int j) -> int64_t { return boffs[j]; };
+  auto fetch_off = [&](int j) -> int64_t { return boffs[jb + j]; };
   auto request_k_at = [&](int64_t off, int slot) { dma_1k(pool + off, voff_k, dma_lds + slot * kSlot); };
   auto request_v_at = [&](int64_t off, int slot) {
     dma_1k(pool + half_b + off, voff_v, dma_lds + kVBase + slot * kSlot);
@@ -237,7 +240,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   // their V is written as zeros so that undefined pool bytes cannot reach the PV product
   auto request_tail = [&](int j) {
     const int64_t boff = fetch_off(j);
-    const bool live = j * kSK + wblk * 16 + brow < ctx_len;
+    const bool live = (jb + j) * kSK + wblk * 16 + brow < ctx_len;
     const unsigned l_k = dma_lds + (j & (kRing - 1)) * kSlot;
     if (live) {
       dma_1k(pool + boff, voff_k, l_k);
@@ -582,7 +585,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     request_tail(j);
     wait_vm<0>();
     __syncthreads();
-    const int k0 = j * kSK;
+    const int k0 = (jb + j) * kSK;
     if (wave_active && k0 <= pq_max) {
       f32x16 s;
       qk(j & 7, s);
@@ -602,6 +605,27 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pv(j & 7, pb);
     }
     __syncthreads();
+  }
+
+  // ---- one piece of a split tile: leave the unnormalised O, the reference and the row sum for
+  // merge_splits_kernel.  Lane holds d = 32dt + 8(r/4) + 4lh + r%4 of query row ln.
+  if (wi.n_splits > 1) {
+    if (wave_active && wq0 + ln < S) {
+      const int64_t slot = ((int64_t)it * NHG + hg) * NW + wave;
+      float* po = p.part_o + (slot * 32 + ln) * kD + 4 * lh;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+        for (int rq = 0; rq < 4; rq++)
+          *(f32x4*)(po + 32 * dt + 8 * rq) = (f32x4){o[dt][4 * rq], o[dt][4 * rq + 1], o[dt][4 * rq + 2], o[dt][4 * rq + 3]};
+      const float lt = half_swap_sum(l_run);
+      if (lh == 0) {
+        float* pm = p.part_ml + (slot * 32 + ln) * 2;
+        pm[0] = m_run;
+        pm[1] = lt;
+      }
+    }
+    return;
   }
 
   // ---- normalise and write O[token][head][d]; lane holds d = 32dt + 8(r/4) + 4lh + r%4
@@ -628,6 +652,62 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   }
 }
 
+// Combines the pieces of split tiles: for every row and head, with m = max_c m_c,
+//     O = sum_c 2^(c2 (m_c - m)) O_c  /  sum_c 2^(c2 (m_c - m)) l_c
+// (the pieces' O_c, l_c are sums of weights 2^(c2 (score - m_c))).  One workgroup of 256 threads per
+// (split tile, head group, wave slot): thread = (row 0..31, 16-float chunk 0..7).  A piece in which
+// a row saw no key has l_c = 0 and m_c = -inf and drops out.
+__global__ void __launch_bounds__(256) merge_splits_kernel(AttnParams p, const int32_t* split_tiles) {
+  constexpr int NW = 8;
+  const int HW = p.heads_per_wg, NHG = p.n_q_heads / HW, TPW = NW / HW;
+  const int wave_slot = blockIdx.x % NW;
+  const int hg = (blockIdx.x / NW) % NHG;
+  const int first = split_tiles[blockIdx.x / (NW * NHG)];
+  const WorkItem wi = p.items[first];
+  const ReqDesc rd = p.reqs[wi.req];
+  const int row = threadIdx.x >> 3, chunk = threadIdx.x & 7;
+  const int tokq = wi.q_tile * 32 * TPW + (wave_slot / HW) * 32 + row;
+  if (tokq >= rd.suffix_len) return;
+  const int hq = hg * HW + wave_slot % HW;
+  const float c2 = p.scale * 1.4426950408889634f;
+  float m = -INFINITY;
+  for (int c = 0; c < wi.n_splits; c++) {
+    const int64_t slot = ((int64_t)(first + c) * NHG + hg) * NW + wave_slot;
+    m = fmaxf(m, p.part_ml[(slot * 32 + row) * 2]);
+  }
+  float acc[16], l = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; i++) acc[i] = 0.f;
+  for (int c = 0; c < wi.n_splits; c++) {
+    const int64_t slot = ((int64_t)(first + c) * NHG + hg) * NW + wave_slot;
+    const float mc = p.part_ml[(slot * 32 + row) * 2], lc = p.part_ml[(slot * 32 + row) * 2 + 1];
+    if (!(lc > 0.f)) continue;
+    const float wgt = __builtin_amdgcn_exp2f((mc - m) * c2);
+    l += wgt * lc;
+    const f32x4* po = (const f32x4*)(p.part_o + (slot * 32 + row) * kD + 16 * chunk);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const f32x4 v = po[i];
+      acc[4 * i] += wgt * v[0]; acc[4 * i + 1] += wgt * v[1]; acc[4 * i + 2] += wgt * v[2]; acc[4 * i + 3] += wgt * v[3];
+    }
+  }
+  const float inv = 1.f / l;
+  unsigned short* out = (unsigned short*)p.out + ((int64_t)(rd.q_off + tokq) * p.n_q_heads + hq) * kD + 16 * chunk;
+  u32x4 w0, w1;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    bf16x2 a, b;
+    a[0] = (__bf16)(acc[2 * i] * inv);
+    a[1] = (__bf16)(acc[2 * i + 1] * inv);
+    b[0] = (__bf16)(acc[8 + 2 * i] * inv);
+    b[1] = (__bf16)(acc[8 + 2 * i + 1] * inv);
+    w0[i] = __builtin_bit_cast(unsigned int, a);
+    w1[i] = __builtin_bit_cast(unsigned int, b);
+  }
+  *(u32x4*)out = w0;
+  *(u32x4*)(out + 8) = w1;
+}
+
 }  // namespace pipe
 
 int attn_pipe_tile_tokens(int heads_per_wg) { return 32 * (8 / heads_per_wg); }
@@ -643,6 +723,13 @@ hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream) {
   }
   const unsigned grid = (unsigned)p.n_items * (unsigned)(p.n_q_heads / p.heads_per_wg);
   hipLaunchKernelGGL(pipe::attn_pipe_kernel, dim3(grid), dim3(512), pipe::kLdsBytes, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_splits(const AttnParams& p, const int32_t* split_tiles, int n_split_tiles, hipStream_t stream) {
+  if (n_split_tiles <= 0) return hipSuccess;
+  const unsigned grid = (unsigned)n_split_tiles * (unsigned)(p.n_q_heads / p.heads_per_wg) * 8u;
+  hipLaunchKernelGGL(pipe::merge_splits_kernel, dim3(grid), dim3(256), 0, stream, p, split_tiles);
   return hipGetLastError();
 }
 

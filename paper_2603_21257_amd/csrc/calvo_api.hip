@@ -79,6 +79,11 @@ struct calvo_ctx {
   std::vector<hipEvent_t> ev_t0, ev_t1;
   std::vector<char> timed;
   int scatter_grid = 64;
+  int force_splits = 0;           // CALVO_ATTN_SPLITS: pieces per tile (0 = automatic)
+  int split_min = 48, split_target = 256;   // shortest piece in sub-tiles; workgroups aimed at (one per CU)
+  float* part_o = nullptr;        // split-KV partial results (compute stream only)
+  float* part_ml = nullptr;
+  size_t part_slots = 0;          // capacity in (work item, head group, wave) slots
   int device = 0;
   // ---- emulated L3 -> L2 stage: a loader thread, a ring of pinned buffers, and the hand-over
   // state it shares with the calling thread (layer_issued, l3_*: guarded by mu)
@@ -116,6 +121,8 @@ void destroy_partial(calvo_ctx* c) {
   if (c->h_tab_ing) (void)hipHostFree(c->h_tab_ing);
   if (c->d_att) (void)hipFree(c->d_att);
   if (c->h_att) (void)hipHostFree(c->h_att);
+  if (c->part_o) (void)hipFree(c->part_o);
+  if (c->part_ml) (void)hipFree(c->part_ml);
   for (auto& s : c->s_copy) if (s) (void)hipStreamDestroy(s);
   if (c->s_scatter) (void)hipStreamDestroy(c->s_scatter);
   if (c->own_compute && c->s_compute) (void)hipStreamDestroy(c->s_compute);
@@ -385,6 +392,12 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->n_staging = cfg->staging_bytes ? (cfg->n_staging ? cfg->n_staging : 2) : 0;
   c->n_copy = cfg->n_copy_streams ? cfg->n_copy_streams : 1;
   c->staging_blocks = cfg->staging_bytes / c->blk_bytes;
+  if (const char* e = getenv("CALVO_ATTN_SPLITS")) {    // test knob: cut every tile's context into this many pieces
+    const int g = atoi(e);
+    if (g >= 1 && g <= 64) c->force_splits = g;
+  }
+  if (const char* e = getenv("CALVO_SPLIT_MIN")) { const int g = atoi(e); if (g >= 1 && g <= 4096) c->split_min = g; }
+  if (const char* e = getenv("CALVO_SPLIT_TARGET")) { const int g = atoi(e); if (g >= 1 && g <= 65536) c->split_target = g; }
   if (const char* e = getenv("CALVO_SCATTER_GRID")) {   // tuning knob: workgroups of the zero-copy scatter
     const int g = atoi(e);
     if (g >= 1 && g <= 4096) c->scatter_grid = g;
@@ -703,19 +716,48 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     blob.push_back(cu_suffix[r]);
     n_tab += (size_t)nt + kTablePad + (nt & 1);
   }
-  struct Item { int32_t req, tile; int64_t cost; };
-  std::vector<Item> items;
+  // Work items.  A tile of suffix tokens normally is one item that walks its whole context.  When
+  // the batch has too few tiles to give every CU a workgroup (short suffixes over long contexts),
+  // every tile's context is cut into pieces of at least split_min sub-tiles that run as separate
+  // workgroups and are merged afterwards; the number of pieces aims at one workgroup per CU
+  // (measured best: more, shorter pieces pay the pipeline fill and drain more often).  Tiles are ordered heaviest first; the pieces of a tile are consecutive.
+  struct Tile { int32_t req, tile, n_sub; };
+  std::vector<Tile> tiles;
+  std::vector<WorkItem> items;
+  std::vector<int32_t> split_tiles;
   if (mfma) {
     for (int r = 0; r < n_reqs; r++) {
       const int nt = (reqs[r].suffix_len + tile_tokens - 1) / tile_tokens;
-      for (int t = 0; t < nt; t++)
-        items.push_back({r, t, (int64_t)reqs[r].n_prefix_blocks * kBlockTokens +
-                                   std::min<int64_t>((int64_t)(t + 1) * tile_tokens, reqs[r].suffix_len)});
+      for (int t = 0; t < nt; t++) {
+        const int64_t keys = (int64_t)reqs[r].n_prefix_blocks * kBlockTokens +
+                             std::min<int64_t>((int64_t)(t + 1) * tile_tokens, reqs[r].suffix_len);
+        tiles.push_back({r, t, (int32_t)((keys + 31) / 32)});
+      }
     }
-    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
+    std::stable_sort(tiles.begin(), tiles.end(), [](const Tile& a, const Tile& b) { return a.n_sub > b.n_sub; });
+    const int64_t wgs = (int64_t)tiles.size() * (cf.n_q_heads / HW);
+    int want = 1;
+    if (attn_mfma_splits_context()) {
+      if (c->force_splits) want = c->force_splits;
+      else if (wgs > 0) want = (int)std::max<int64_t>(1, std::min<int64_t>(64, c->split_target / wgs));
+    }
+    for (const Tile& t : tiles) {
+      int n = std::max(1, std::min(want, c->force_splits ? t.n_sub : t.n_sub / c->split_min));
+      const int len = (t.n_sub + n - 1) / n;
+      n = (t.n_sub + len - 1) / len;
+      const int32_t first = (int32_t)items.size();
+      if (n > 1) split_tiles.push_back(first);
+      for (int k = 0; k < n; k++)
+        items.push_back({t.req, t.tile, k * len, std::min(t.n_sub, (k + 1) * len), n, first, 0, 0});
+    }
   }
   const size_t items_off = blob.size();
-  for (const Item& it : items) { blob.push_back(it.req); blob.push_back(it.tile); }
+  for (const WorkItem& it : items) {
+    const int32_t* w = (const int32_t*)&it;
+    blob.insert(blob.end(), w, w + sizeof(WorkItem) / 4);
+  }
+  const size_t split_off = blob.size();
+  blob.insert(blob.end(), split_tiles.begin(), split_tiles.end());
   const size_t tables_off = blob.size();
   for (int r = 0; r < n_reqs; r++) {
     const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
@@ -741,6 +783,19 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
 
   rc = ensure_att_blob(c, blob.size());
   if (rc != CALVO_OK) return rc;
+  if (!split_tiles.empty()) {
+    const size_t slots = items.size() * (size_t)(cf.n_q_heads / HW) * 8;
+    if (slots > c->part_slots) {
+      HIP_TRY(hipStreamSynchronize(c->s_compute));
+      if (c->part_o) (void)hipFree(c->part_o);
+      if (c->part_ml) (void)hipFree(c->part_ml);
+      c->part_o = c->part_ml = nullptr;
+      c->part_slots = 0;
+      HIP_TRY(hipMalloc((void**)&c->part_o, slots * 32 * 128 * sizeof(float)));
+      HIP_TRY(hipMalloc((void**)&c->part_ml, slots * 32 * 2 * sizeof(float)));
+      c->part_slots = slots;
+    }
+  }
   const bool same = c->att_len == blob.size() && memcmp(c->h_att, blob.data(), blob.size() * 4) == 0;
   if (!same) {
     if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
@@ -777,7 +832,10 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
   if (mfma) {
     p.n_items = (int32_t)items.size();
+    p.part_o = c->part_o;
+    p.part_ml = c->part_ml;
     HIP_TRY(launch_attn_mfma(p, c->s_compute));
+    HIP_TRY(launch_merge_splits(p, c->d_att + split_off, (int)split_tiles.size(), c->s_compute));
   } else {
     p.n_items = n_reqs;
     HIP_TRY(launch_attn_simple(p, cf.dtype, total, c->s_compute));

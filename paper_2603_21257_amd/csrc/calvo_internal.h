@@ -14,10 +14,18 @@ struct ReqDesc {
   int32_t q_off;      // first row of this request inside q / out / k_suffix / v_suffix
 };
 
-// One unit of attention work: a tile of suffix tokens of one request.
+// One unit of attention work: a tile of suffix tokens of one request and a range of 32-key
+// sub-tiles of its context.  A tile whose context is cut into n_splits > 1 ranges produces partial
+// results (unnormalised O, running maximum, row sum) that merge_splits_kernel combines; the pieces
+// of one tile are consecutive work items.
 struct WorkItem {
   int32_t req;
   int32_t q_tile;     // tile index inside the request's suffix
+  int32_t sub_begin;  // first 32-key sub-tile of this piece
+  int32_t sub_end;    // one past its last sub-tile (the last piece ends at the tile's causal limit)
+  int32_t n_splits;   // pieces the tile is cut into; 1 = the kernel writes the final output itself
+  int32_t first_item; // index of the tile's first piece
+  int32_t pad0, pad1;
 };
 
 struct AttnParams {
@@ -33,6 +41,11 @@ struct AttnParams {
   int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
   int32_t tile_tokens;      // suffix tokens per work item
   float scale;              // softmax scale (natural-exponent units)
+  // split-KV partial results, used by work items with n_splits > 1: per work item, head group, wave
+  // (head of the group x 32-token half of the tile): part_o [32 rows][D] fp32 unnormalised,
+  // part_ml [32 rows][2] = (running maximum in score units, row sum)
+  float* part_o;
+  float* part_ml;
   long long* prof;          // phase-timing builds only (CALVO_PHASE_PROF): one counter per wave, else NULL
 };
 
@@ -54,7 +67,11 @@ hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
 hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
 int attn_mfma_tile_tokens(int heads_per_wg);
+bool attn_mfma_splits_context();   // whether the selected MFMA kernel handles work items with n_splits > 1
 hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
+// combines the pieces of every split tile into out (bf16); n_split_tiles entries in split_tiles =
+// indices of the first work item of each split tile
+hipError_t launch_merge_splits(const AttnParams& p, const int32_t* split_tiles, int n_split_tiles, hipStream_t stream);
 int attn_pipe_tile_tokens(int heads_per_wg);
 
 constexpr int kBlockTokens = 16;

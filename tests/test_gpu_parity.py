@@ -65,6 +65,25 @@ def test_bf16_scores_that_outgrow_the_softmax_reference(pattern):
     check(w)
 
 
+@pytest.mark.parametrize("lens", [[(16384, 20)], [(8192, 64)], [(12000, 1)], [(4096, 3), (8192, 70), (2048, 0), (6144, 130)]])
+def test_bf16_short_suffix_over_long_context_uses_split_kv(lens):
+    """Few suffix tokens over a long context: the library cuts every tile's context into pieces that run
+    as separate workgroups and merges them (the paper's regime: long reused context, short query)."""
+    shape = wl.Shape(2, 8, 2, 128, "bf16", sum(-(-(p + s) // 16) for p, s in lens) + 5)
+    w = wl.make_custom(shape, lens, seed=700 + len(lens) + lens[0][1])
+    check(w)
+
+
+@pytest.mark.parametrize("n_splits", [2, 5, 64])
+def test_bf16_forced_context_splits(n_splits, monkeypatch):
+    """Every tile cut into n pieces (down to single 32-key sub-tiles), including the pieces that hold
+    the causal diagonal and the ragged end of the context."""
+    monkeypatch.setenv("CALVO_ATTN_SPLITS", str(n_splits))
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 128)
+    w = wl.make_custom(shape, [(1024, 200), (48, 77), (0, 130)], seed=800 + n_splits)
+    check(w)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2), (6, 2), (12, 4)])
 def test_bf16_mfma_gqa_group_sizes(Hq, Hkv):
     shape = wl.Shape(1, Hq, Hkv, 128, "bf16", 64)
