@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload recipe 1..5 (default 3: 64K context)")
+    ap.add_argument("--config", type=int, default=3, help="workload recipe 1..7 (default 3: 64K context)")
     ap.add_argument("--staging-mib", type=int, default=-1,
                     help="size of each device staging buffer of the copy-engine ingest; 0 = zero-copy kernel "
                          "ingest; -1 = one layer of the workload's prefix bytes (at most 512 MiB)")

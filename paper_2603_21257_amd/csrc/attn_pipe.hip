@@ -502,7 +502,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pv((t - 1) & 7, pbuf[N]);
     }
     if (t < n_pipe) sm_all(sbuf[C], pbuf[C], al[C], chg[C]);
-    wait_vm<0>();
+    wait_vm<8>();      // as in a steady step: K up to t+3 and V up to t+1 have landed
     __syncthreads();
   };
 
@@ -580,7 +580,11 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     else step_edge(Tag<0>{}, t);
   }
 
-  // ---- sub-tiles on or past the diagonal: synchronous load, plain path
+  // ---- sub-tiles on or past the diagonal: synchronous load, plain path.  The ring slots are
+  // written again below (by requests and, for rows past the context, by plain LDS stores), so
+  // every request of the pipelined part has to have landed first.
+  wait_vm<0>();
+  __syncthreads();
   for (int j = n_pipe; j < n_sub; j++) {
     request_tail(j);
     wait_vm<0>();

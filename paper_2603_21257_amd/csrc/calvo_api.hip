@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <mutex>
 #include <new>
 #include <string>
@@ -80,7 +81,11 @@ struct calvo_ctx {
   std::vector<char> timed;
   int scatter_grid = 64;
   int force_splits = 0;           // CALVO_ATTN_SPLITS: pieces per tile (0 = automatic)
-  int split_min = 48, split_target = 256;   // shortest piece in sub-tiles; workgroups aimed at (one per CU)
+  int split_min = 48;             // shortest piece of a cut tile, in 32-key sub-tiles
+  int split_fill = 30;            // cost of a workgroup's pipeline fill and drain, in sub-tile steps (launch replay)
+  int n_cus = 256;                // compute units of the device
+  std::vector<int64_t> plan_key;  // lengths of the batch the cached decision belongs to
+  int plan_want = 1;
   float* part_o = nullptr;        // split-KV partial results (compute stream only)
   float* part_ml = nullptr;
   size_t part_slots = 0;          // capacity in (work item, head group, wave) slots
@@ -386,6 +391,11 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   if (!c) return fail(CALVO_ENOMEM, "out of host memory");
   c->cfg = *cfg;
   c->device = dev;
+  {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) c->n_cus = cus;
+    else (void)hipGetLastError();
+  }
   c->elt = cfg->dtype == CALVO_BF16 ? 2 : 4;
   c->blk_bytes = (size_t)2 * kBlockTokens * cfg->n_kv_heads * cfg->head_dim * c->elt;
   c->layer_bytes = (int64_t)cfg->pool_blocks * (int64_t)c->blk_bytes;
@@ -397,7 +407,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
     if (g >= 1 && g <= 64) c->force_splits = g;
   }
   if (const char* e = getenv("CALVO_SPLIT_MIN")) { const int g = atoi(e); if (g >= 1 && g <= 4096) c->split_min = g; }
-  if (const char* e = getenv("CALVO_SPLIT_TARGET")) { const int g = atoi(e); if (g >= 1 && g <= 65536) c->split_target = g; }
+  if (const char* e = getenv("CALVO_SPLIT_FILL")) { const int g = atoi(e); if (g >= 0 && g <= 4096) c->split_fill = g; }
   if (const char* e = getenv("CALVO_SCATTER_GRID")) {   // tuning knob: workgroups of the zero-copy scatter
     const int g = atoi(e);
     if (g >= 1 && g <= 4096) c->scatter_grid = g;
@@ -735,16 +745,71 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
       }
     }
     std::stable_sort(tiles.begin(), tiles.end(), [](const Tile& a, const Tile& b) { return a.n_sub > b.n_sub; });
-    const int64_t wgs = (int64_t)tiles.size() * (cf.n_q_heads / HW);
+    const int NHG = cf.n_q_heads / HW;
+    const int64_t wgs = (int64_t)tiles.size() * NHG;
+    // pieces a tile of n_sub sub-tiles is cut into when `want` are asked for
+    // length of the pieces a tile of n_sub sub-tiles is cut into when `want` pieces are asked for.
+    // The kernel runs a piece of n sub-tiles as one fill step, 8-step steady iterations and
+    // n - 8k >= 2 slower drain steps, so lengths of the form 8k + 2 waste the least.
+    auto piece_len = [&](int n_sub, int want) {
+      const int n = std::max(1, std::min(want, c->force_splits ? n_sub : n_sub / c->split_min));
+      int len = (n_sub + n - 1) / n;
+      if (n > 1 && !c->force_splits) len = (len + 5) / 8 * 8 + 2;
+      return len;
+    };
     int want = 1;
     if (attn_mfma_splits_context()) {
       if (c->force_splits) want = c->force_splits;
-      else if (wgs > 0) want = (int)std::max<int64_t>(1, std::min<int64_t>(64, c->split_target / wgs));
+      else if (wgs > 0 && wgs <= 16 * (int64_t)c->n_cus) {
+        // Choose the number of pieces by replaying the launch: workgroups start in grid order on
+        // the first free CU (one workgroup per CU), a piece costs its sub-tiles plus a fixed
+        // pipeline fill and drain, cut tiles pay the merge.  This covers both too few workgroups
+        // for the chip and a workgroup count just above a whole number of rounds (640 equal
+        // workgroups on 256 CUs take three rounds; cut in two they take five half-length rounds).
+        // The decision depends only on the batch's lengths and is kept for the following layers.
+        std::vector<int64_t> key;
+        key.reserve(2 * n_reqs);
+        for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
+        if (key == c->plan_key) want = c->plan_want;
+        else {
+          const int cands[] = {1, 2, 3, 4, 5, 6, 8, 12, 16, 24, 32, 48, 64};
+          double best = 0;
+          std::vector<int64_t> heap;
+          for (int n : cands) {
+            if (n > 1 && wgs * n > 16 * (int64_t)c->n_cus) break;
+            heap.assign((size_t)c->n_cus, 0);            // min-heap of the times at which CUs become free
+            auto cmp = std::greater<int64_t>();
+            bool cut = false;
+            int64_t end = 0;
+            for (const Tile& t : tiles) {
+              const int len = piece_len(t.n_sub, n);
+              const int np = (t.n_sub + len - 1) / len;
+              cut |= np > 1;
+              for (int k = 0; k < np; k++) {
+                const int64_t cost = std::min(t.n_sub, (k + 1) * len) - k * len + c->split_fill;
+                for (int h = 0; h < NHG; h++) {
+                  std::pop_heap(heap.begin(), heap.end(), cmp);
+                  heap.back() += cost;
+                  end = std::max(end, heap.back());
+                  std::push_heap(heap.begin(), heap.end(), cmp);
+                }
+              }
+            }
+            const double span = (double)end + (cut ? c->split_fill : 0);
+            if (n == 1 || span < best * 0.98) {          // a cut has to win by 2 % over what is chosen so far
+              best = span;
+              want = n;
+            }
+            if (!cut && n > 1) break;                     // longer cuts are refused by split_min: nothing changes
+          }
+          c->plan_key = key;
+          c->plan_want = want;
+        }
+      }
     }
     for (const Tile& t : tiles) {
-      int n = std::max(1, std::min(want, c->force_splits ? t.n_sub : t.n_sub / c->split_min));
-      const int len = (t.n_sub + n - 1) / n;
-      n = (t.n_sub + len - 1) / len;
+      const int len = piece_len(t.n_sub, want);
+      const int n = (t.n_sub + len - 1) / len;
       const int32_t first = (int32_t)items.size();
       if (n > 1) split_tiles.push_back(first);
       for (int k = 0; k < n; k++)

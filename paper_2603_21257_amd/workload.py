@@ -225,11 +225,18 @@ CONFIG_NAMES = {
     3: "cfg3: Llama-3-8B-shaped stack, 32 layers, 32Q/8KV, D=128, bf16, P=61440, S=4096 (64K ctx)",
     4: "cfg4: same shape, 8 varlen requests sharing a 4096-token run, pool 40000",
     5: "cfg5: Qwen2.5-72B-shaped stack, 80 layers, 64Q/8KV, D=128, bf16, P=122880, S=8192",
+    6: "cfg6: Qwen2.5-14B-shaped stack, 48 layers, 40Q/8KV (group of 5), D=128, bf16, P=61440, S=4096",
+    7: "cfg7: Llama-3-8B-shaped stack, 3 requests with the mean context/query lengths of the paper's Table 1 "
+       "(28096+28, 28304+61, 38304+209)",
 }
+
+# Mean (context, query) token counts of the three datasets in the paper's Table 1, contexts
+# rounded down to whole 16-token blocks: long context, short query.
+TABLE1_MEAN_LENGTHS = [(28096, 28), (28304, 61), (38304, 209)]
 
 
 def config_shape_and_requests(cfg: int, seed: int = BASE_SEED, n_layers: Optional[int] = None):
-    """Shapes, tables and lengths of one of the five workload recipes (no payload)."""
+    """Shapes, tables and lengths of one of the workload recipes (no payload)."""
     if cfg == 1:
         shape = Shape(1, 8, 2, 64, "f32", 256)
         reqs = single_request(shape, 1024, 128, seed)
@@ -246,6 +253,17 @@ def config_shape_and_requests(cfg: int, seed: int = BASE_SEED, n_layers: Optiona
         need = (P + S) // BLOCK_TOKENS
         shape = Shape(n_layers or 80, 64, 8, 128, "bf16", need * 5 // 4)
         reqs = single_request(shape, P, S, seed)
+    elif cfg == 6:
+        # second model family of the paper's evaluation (Section 4.1): 48 layers, 40 query heads in
+        # 8 KV groups of 5 - a group size the 4-heads-per-workgroup tiling does not divide
+        P, S = 61440, 4096
+        need = (P + S) // BLOCK_TOKENS
+        shape = Shape(n_layers or 48, 40, 8, 128, "bf16", need * 5 // 4)
+        reqs = single_request(shape, P, S, seed)
+    elif cfg == 7:
+        need = sum(p // BLOCK_TOKENS + -(-q // BLOCK_TOKENS) for p, q in TABLE1_MEAN_LENGTHS)
+        shape = Shape(n_layers or 32, 32, 8, 128, "bf16", need * 5 // 4)
+        return shape, make_custom(shape, TABLE1_MEAN_LENGTHS, seed, with_payload=False).requests
     else:
         raise ValueError(f"unknown config {cfg}")
     return shape, reqs
@@ -267,7 +285,7 @@ def _finish(name, shape, reqs, seed, with_payload) -> Workload:
 
 def make_config(cfg: int, seed: int = BASE_SEED, n_layers: Optional[int] = None,
                 with_payload: Optional[bool] = None) -> Workload:
-    """Workload recipe cfg (1..5).  Payload arrays are drawn with numpy only when
+    """Workload recipe cfg (1..7).  Payload arrays are drawn with numpy only when
     asked for (default: config 1 only); large payloads are produced with
     fill_normal_ into buffers the caller allocates."""
     shape, reqs = config_shape_and_requests(cfg, seed, n_layers)

@@ -135,3 +135,14 @@ def test_workload4_full_size_varlen_batch_shared_prefix():
     """8 varlen requests sharing a 4096-token run, pool of 40000 blocks per layer (78 GiB)."""
     w = run_full(4, pool_layers=[0, 31], attn_layers=[0, 31], rows_per_req=16)
     assert len(w.requests) == 8 and all(r.first_ingest_block == 256 for r in w.requests[1:])
+
+
+def test_workload6_full_size_group_of_five():
+    """Qwen2.5-14B-shaped stack (48 layers, 40Q/8KV): one query head per workgroup, eight token tiles."""
+    run_full(6, pool_layers=[0, 47], attn_layers=[0, 47], rows_per_req=24)
+
+
+def test_workload7_full_size_table1_lengths_split_kv():
+    """Three requests with the paper's Table 1 mean lengths (28-209 query tokens over 28K-38K cached
+    tokens): the regime the paper serves; every tile's context is cut into pieces and merged."""
+    run_full(7, pool_layers=[0, 31], attn_layers=[0, 16, 31], rows_per_req=28)
