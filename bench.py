@@ -59,6 +59,11 @@ def main():
                     help="skip the extra measurement with the emulated remote store in front (L3 -> L2 -> L1 -> compute)")
     ap.add_argument("--l3-gbps", type=float, default=50.0, help="emulated L3 link rate (paper Section 4.1: 400 Gbps)")
     ap.add_argument("--sample-rows", type=int, default=512)
+    ap.add_argument("--tail-chunks", type=int, default=-1,
+                    help="load each of the last --tail-layers layers in this many chunks with one readiness signal each, so "
+                         "that their attention starts on the chunks that have landed (0 = whole layers only; -1 = 4 if loading "
+                         "alone takes longer than attention alone on this workload, else 0)")
+    ap.add_argument("--tail-layers", type=int, default=6)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -127,8 +132,24 @@ def main():
         pool.view(torch.int16 if tdt == torch.bfloat16 else torch.int32).fill_(0x7FC1 if tdt == torch.bfloat16 else 0x7FC12345)
         torch.cuda.synchronize()
 
+    # chunk-granular readiness for the last layers: their attention cannot hide behind the loading of
+    # later layers, and starting it on landed chunks moves compute-stream work forward
+    plan = {"chunk_blocks": None}
+
+    def set_tail_chunks(n):
+        if n <= 0 or L < 1:
+            plan["chunk_blocks"] = None
+            return
+        longest = max(r.n_prefix_blocks for r in w.requests)
+        per = max(2, -(-longest // n))
+        nt = max(1, min(L, args.tail_layers))
+        plan["chunk_blocks"] = [0] * (L - nt) + [per + (per & 1)] * nt
+
     def step():
-        cb.calvo_kv_ingest(ctx, reqs, 0, L)
+        if plan["chunk_blocks"] is None:
+            cb.calvo_kv_ingest(ctx, reqs, 0, L)
+        else:
+            cb.calvo_kv_ingest_chunked(ctx, reqs, 0, L, plan["chunk_blocks"])
         for l in range(L):
             cb.calvo_prefill_attn(ctx, l, q[l], ks[l], vs[l], out[l], reqs, w.cu_suffix, 0.0)
         torch.cuda.synchronize()
@@ -160,17 +181,23 @@ def main():
             t = [timed(fn) for _ in range(args.steps)]
             log(f"[bench] mode {args.mode}: {statistics.mean(t):.3f} ms per pass over {L} layers")
             return
-        for _ in range(args.warmup):
-            step()
-        # ---- stage times in isolation (context for the overlap figure)
+        # ---- stage times in isolation (context for the overlap figure, and the choice of the chunked tail)
+        ingest_only()
         t_ing = min(timed(ingest_only) for _ in range(2))
         t_att = min(timed(attn_only) for _ in range(2))
+        if args.tail_chunks < 0:
+            args.tail_chunks = 4 if t_ing > t_att else 0
+        set_tail_chunks(args.tail_chunks)
+        for _ in range(args.warmup):
+            step()
         # ---- the timed steps
         step_ms, kern_ms = [], []
         for _ in range(args.steps):
             poison()
             step_ms.append(timed(step))
-            kern_ms.extend(cb.calvo_attn_kernel_ms(ctx, l) for l in range(L))
+            # whole-layer launches only: the event pair of a chunk-granular layer also spans its waits
+            cbs = plan["chunk_blocks"]
+            kern_ms.extend(cb.calvo_attn_kernel_ms(ctx, l) for l in range(L) if not (cbs and cbs[l]))
         ms = statistics.mean(step_ms)
         k_ms = statistics.mean(kern_ms)
         flop_per_launch = w.attn_flop() / L
@@ -190,7 +217,8 @@ def main():
                        "head_dim": s.head_dim, "block_tokens": s.block_tokens,
                        "prefix_tokens": [r.prefix_len for r in w.requests],
                        "suffix_tokens": [r.suffix_len for r in w.requests],
-                       "ingest": "zero-copy kernel" if args.staging_mib == 0 else f"copy engine, {args.staging_mib} MiB staging x{args.n_staging or 2}"},
+                       "ingest": "zero-copy kernel" if args.staging_mib == 0 else f"copy engine, {args.staging_mib} MiB staging x{args.n_staging or 2}",
+                       "chunked_tail": f"{args.tail_layers} layers x {args.tail_chunks} chunks" if args.tail_chunks else "none"},
             "ttft_ms": {"mean": round(ms, 3), "median": round(statistics.median(step_ms), 3),
                         "min": round(min(step_ms), 3), "lower_bound": round(ttft_lb, 3),
                         "frac_of_lower_bound": round(ttft_lb / ms, 4)},

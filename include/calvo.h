@@ -103,6 +103,31 @@ int calvo_destroy(calvo_ctx* ctx);
  * blocks; CALVO_EHIP if HIP refuses a transfer (queued work so far still completes). */
 int calvo_kv_ingest(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end);
 
+/* Chunk-granular readiness (paper Section 3.1: "each time a stage completes loading a KVCache
+ * block, it would issue a signal to the upper-level stage" so that the stage above can start on what
+ * has landed).  Same loads and same final pool bytes as calvo_kv_ingest; in addition layer l (entry
+ * l - layer_begin of chunk_blocks, HOST array of layer_end - layer_begin entries) is loaded in chunks
+ * of chunk_blocks block indices: chunk k = blocks [k*cb, (k+1)*cb) of every request's table, chunks in
+ * ascending order, one event per chunk recorded after its last store.  When chunk k's event has fired,
+ * blocks [0, (k+1)*cb) of every request are resident in layer l (a shared run occupies the same
+ * indices in every table).  An entry of 0 loads that layer as a whole (no chunk events).  Entries
+ * must be even (attention walks the context two blocks at a time) and non-negative.
+ * calvo_prefill_attn on a layer loaded this way starts on each chunk's keys as soon as that chunk is
+ * in - one launch per chunk over partial softmax results, merged at the end - instead of waiting for
+ * the whole layer; its result is the same up to rounding.  Every transfer boundary costs PCIe time,
+ * so chunks pay where the wait for a whole layer is exposed (the last layer of a load-bound
+ * request, the first of a compute-bound one).  Errors as calvo_kv_ingest, plus CALVO_EINVAL for a
+ * NULL or odd / negative chunk_blocks entry. */
+int calvo_kv_ingest_chunked(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end,
+                            const int32_t* chunk_blocks);
+
+/* Number of chunks the most recent load of `layer` was cut into (0: loaded as a whole or never). */
+int calvo_chunk_count(calvo_ctx* ctx, int layer, int* n_chunks);
+
+/* The per-chunk signal: modes as calvo_layer_event.  CALVO_EINVAL if chunk is outside
+ * [0, calvo_chunk_count(layer)). */
+int calvo_chunk_event(calvo_ctx* ctx, int layer, int chunk, int mode, void* stream);
+
 /* Three-stage loading: remote store (L3) -> local host DRAM (L2) -> HBM (L1), each stage moving a
  * block as soon as its source is ready and its destination is free, and signalling the stage above
  * (paper Section 3.1; Section 4.1 gives the L3 link as 400 Gbps).  The remote store is emulated:

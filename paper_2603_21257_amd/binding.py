@@ -21,8 +21,8 @@ CALVO_BF16, CALVO_F32 = 0, 1
 CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
-EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_l3", "calvo_l3_wait",
-           "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_cost_fit", "calvo_cost_estimate",
+EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_last_error"]
 CALVO_POLICY_FIFO, CALVO_POLICY_SJF, CALVO_POLICY_SJF_PT, CALVO_POLICY_LSTF, CALVO_POLICY_EDF = range(5)
 
@@ -78,6 +78,10 @@ def lib() -> C.CDLL:
         L.calvo_create.argtypes = [C.POINTER(calvo_config), C.POINTER(C.c_void_p)]
         L.calvo_destroy.argtypes = [C.c_void_p]
         L.calvo_kv_ingest.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int]
+        L.calvo_kv_ingest_chunked.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int,
+                                              C.POINTER(C.c_int32)]
+        L.calvo_chunk_count.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]
+        L.calvo_chunk_event.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.calvo_kv_ingest_l3.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.c_int, C.c_int,
                                          C.POINTER(calvo_l3_config)]
         L.calvo_l3_wait.argtypes = [C.c_void_p, C.POINTER(calvo_l3_stats)]
@@ -154,6 +158,28 @@ def calvo_destroy(ctx: int) -> None:
 
 def calvo_kv_ingest(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int) -> None:
     _check(lib().calvo_kv_ingest(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end))
+
+
+def calvo_kv_ingest_chunked(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int,
+                            chunk_blocks) -> None:
+    """chunk_blocks: one even block count per layer of the range (0 = load that layer as a whole)."""
+    cb = np.ascontiguousarray(chunk_blocks, dtype=np.int32)
+    if cb.shape != (layer_end - layer_begin,):
+        raise ValueError("chunk_blocks needs one entry per layer of the range")
+    _check(lib().calvo_kv_ingest_chunked(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end,
+                                         cb.ctypes.data_as(C.POINTER(C.c_int32))))
+
+
+def calvo_chunk_count(ctx: int, layer: int) -> int:
+    n = C.c_int(0)
+    _check(lib().calvo_chunk_count(ctx, layer, C.byref(n)))
+    return n.value
+
+
+def calvo_chunk_event(ctx: int, layer: int, chunk: int, mode: int, stream=None) -> bool:
+    """True when the chunk is resident (always, for the two waiting modes)."""
+    rc = lib().calvo_chunk_event(ctx, layer, chunk, mode, None if stream is None else int(stream))
+    return _check(rc, ok=(CALVO_OK, CALVO_ENOTREADY)) == CALVO_OK
 
 
 def calvo_kv_ingest_l3(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int,

@@ -161,6 +161,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       it = bid / NHG;
     }
   }
+  if (p.item_index) it = p.item_index[it];       // this launch runs a subset of the work items
   const WorkItem wi = p.items[it];
   const ReqDesc rd = p.reqs[wi.req];
   const int P = rd.prefix_len, S = rd.suffix_len;

@@ -64,6 +64,12 @@ struct calvo_ctx {
   uint64_t seq = 0;
   std::vector<hipEvent_t> ev_layer;
   std::vector<char> layer_issued;
+  // chunk-granular readiness: layer l was loaded in pieces of chunk_blocks[l] block indices
+  // (0 = as a whole); ev_chunk[l][k] fires when blocks [0, (k+1) * chunk_blocks[l]) of every
+  // request are resident
+  std::vector<int32_t> chunk_blocks;
+  std::vector<int32_t> n_chunks;
+  std::vector<std::vector<hipEvent_t>> ev_chunk;
   // ingest-side table copy (device) and its pinned shadow
   int32_t* d_tab_ing = nullptr;
   int32_t* h_tab_ing = nullptr;
@@ -115,6 +121,8 @@ void destroy_partial(calvo_ctx* c) {
   for (auto e : c->ev_filled) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_free) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_layer) if (e) (void)hipEventDestroy(e);
+  for (auto& v : c->ev_chunk)
+    for (auto e : v) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_t0) if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_t1) if (e) (void)hipEventDestroy(e);
   for (void* p : c->l2_ring)
@@ -440,6 +448,9 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->ev_t0.assign(cfg->n_layers, nullptr);
   c->ev_t1.assign(cfg->n_layers, nullptr);
   c->layer_issued.assign(cfg->n_layers, 0);
+  c->chunk_blocks.assign(cfg->n_layers, 0);
+  c->n_chunks.assign(cfg->n_layers, 0);
+  c->ev_chunk.resize(cfg->n_layers);
   c->layer_pending.assign(cfg->n_layers, 0);
   c->timed.assign(cfg->n_layers, 0);
   for (int l = 0; l < cfg->n_layers; l++) {
@@ -527,8 +538,14 @@ int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int laye
 
 extern "C" {
 
-int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end) {
+static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end,
+                       const int32_t* chunk_blocks) {
   if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (chunk_blocks && layer_begin >= 0 && layer_end <= c->cfg.n_layers)
+    for (int l = layer_begin; l < layer_end; l++) {
+      const int32_t cb = chunk_blocks[l - layer_begin];
+      if (cb < 0 || (cb & 1)) return fail(CALVO_EINVAL, "chunk_blocks[%d] = %d must be 0 or a positive even number", l - layer_begin, cb);
+    }
   int rc = join_loader(c);
   if (rc != CALVO_OK) return rc;
   std::vector<const unsigned char*> src;
@@ -536,31 +553,106 @@ int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int lay
   rc = prepare_ingest(c, reqs, n_reqs, layer_begin, layer_end, true, src, tab_off);
   if (rc != CALVO_OK) return rc;
   if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
+  int64_t max_blocks = 0;
+  for (int r = 0; r < n_reqs; r++) max_blocks = std::max<int64_t>(max_blocks, reqs[r].n_prefix_blocks);
+
+  // blocks [j0, j1) of request r, layer l: one scatter launch (zero-copy) or staged pieces
+  auto load_range = [&](int l, int r, int64_t j0, int64_t j1) -> int {
+    const calvo_request& q = reqs[r];
+    unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
+    const unsigned char* lsrc = src[r] + (int64_t)l * q.host_layer_stride;
+    if (c->n_staging == 0) {
+      // zero-copy: the scatter kernel reads the pinned blocks over PCIe itself
+      HIP_TRY(launch_scatter_blocks(lsrc + j0 * (int64_t)c->blk_bytes, pool_layer, c->d_tab_ing + tab_off[r] + j0,
+                                    j1 - j0, (int32_t)c->blk_bytes, c->scatter_grid, c->s_scatter));
+      return CALVO_OK;
+    }
+    for (int64_t j = j0; j < j1; j += c->staging_blocks) {
+      const int64_t nb = std::min<int64_t>(c->staging_blocks, j1 - j);
+      HIP_TRY(enqueue_staged(c, lsrc + j * (int64_t)c->blk_bytes, pool_layer, c->d_tab_ing + tab_off[r] + j, nb, nullptr));
+    }
+    return CALVO_OK;
+  };
 
   for (int l = layer_begin; l < layer_end; l++) {
-    unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
-    for (int r = 0; r < n_reqs; r++) {
-      const calvo_request& q = reqs[r];
-      const int64_t first = q.first_ingest_block, nblk = q.n_prefix_blocks;
-      if (nblk == first) continue;
-      const unsigned char* lsrc = src[r] + (int64_t)l * q.host_layer_stride;
-      if (c->n_staging == 0) {
-        // zero-copy: the scatter kernel reads the pinned blocks over PCIe itself
-        HIP_TRY(launch_scatter_blocks(lsrc + first * (int64_t)c->blk_bytes, pool_layer,
-                                      c->d_tab_ing + tab_off[r] + first, nblk - first, (int32_t)c->blk_bytes,
-                                      c->scatter_grid, c->s_scatter));
-      } else {
-        for (int64_t j0 = first; j0 < nblk; j0 += c->staging_blocks) {
-          const int64_t nb = std::min<int64_t>(c->staging_blocks, nblk - j0);
-          HIP_TRY(enqueue_staged(c, lsrc + j0 * (int64_t)c->blk_bytes, pool_layer, c->d_tab_ing + tab_off[r] + j0, nb,
-                                 nullptr));
+    const int64_t cb = chunk_blocks ? chunk_blocks[l - layer_begin] : 0;
+    const int64_t nck = cb > 0 ? (max_blocks + cb - 1) / cb : 0;
+    if (nck > 0) {
+      // events of this layer's chunks (kept for later calls)
+      while ((int64_t)c->ev_chunk[l].size() < nck) {
+        hipEvent_t ev = nullptr;
+        HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        c->ev_chunk[l].push_back(ev);
+      }
+    }
+    if (cb == 0) {
+      for (int r = 0; r < n_reqs; r++)
+        if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block) {
+          rc = load_range(l, r, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks);
+          if (rc != CALVO_OK) return rc;
         }
+    } else {
+      // chunk k = block indices [k cb, (k+1) cb) of every request (a shared run sits at the same
+      // indices in every table, so once chunk k is in, all blocks below (k+1) cb are resident)
+      for (int64_t k = 0; k < nck; k++) {
+        for (int r = 0; r < n_reqs; r++) {
+          const int64_t j0 = std::max<int64_t>(reqs[r].first_ingest_block, k * cb);
+          const int64_t j1 = std::min<int64_t>(reqs[r].n_prefix_blocks, (k + 1) * cb);
+          if (j0 < j1 && (rc = load_range(l, r, j0, j1)) != CALVO_OK) return rc;
+        }
+        HIP_TRY(hipEventRecord(c->ev_chunk[l][k], c->s_scatter));
       }
     }
     HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
     std::lock_guard<std::mutex> lk(c->mu);
     c->layer_issued[l] = 1;
+    c->chunk_blocks[l] = (int32_t)cb;
+    c->n_chunks[l] = (int32_t)nck;
   }
+  return CALVO_OK;
+}
+
+int calvo_kv_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end) {
+  return ingest_impl(c, reqs, n_reqs, layer_begin, layer_end, nullptr);
+}
+
+int calvo_kv_ingest_chunked(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end,
+                            const int32_t* chunk_blocks) {
+  if (!chunk_blocks) return fail(CALVO_EINVAL, "chunk_blocks is NULL");
+  return ingest_impl(c, reqs, n_reqs, layer_begin, layer_end, chunk_blocks);
+}
+
+int calvo_chunk_count(calvo_ctx* c, int layer, int* n_chunks) {
+  if (!c || !n_chunks) return fail(CALVO_EINVAL, "ctx or n_chunks is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  std::lock_guard<std::mutex> lk(c->mu);
+  *n_chunks = c->n_chunks[layer];
+  return CALVO_OK;
+}
+
+int calvo_chunk_event(calvo_ctx* c, int layer, int chunk, int mode, void* stream) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  if (mode != CALVO_EV_QUERY && mode != CALVO_EV_HOST_WAIT && mode != CALVO_EV_STREAM_WAIT)
+    return fail(CALVO_EINVAL, "unknown mode %d", mode);
+  int nck;
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    nck = c->n_chunks[layer];
+  }
+  if (chunk < 0 || chunk >= nck) return fail(CALVO_EINVAL, "chunk %d outside [0, %d) of layer %d", chunk, nck, layer);
+  hipEvent_t ev = c->ev_chunk[layer][chunk];
+  if (mode == CALVO_EV_QUERY) {
+    hipError_t e = hipEventQuery(ev);
+    if (e == hipSuccess) return CALVO_OK;
+    if (e == hipErrorNotReady) { (void)hipGetLastError(); return fail(CALVO_ENOTREADY, "chunk %d of layer %d is still loading", chunk, layer); }
+    return fail_hip(e, "hipEventQuery");
+  }
+  if (mode == CALVO_EV_HOST_WAIT) {
+    HIP_TRY(hipEventSynchronize(ev));
+    return CALVO_OK;
+  }
+  HIP_TRY(hipStreamWaitEvent(stream ? (hipStream_t)stream : c->s_compute, ev, 0));
   return CALVO_OK;
 }
 
@@ -618,7 +710,7 @@ int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
   }
   {
     std::lock_guard<std::mutex> lk(c->mu);
-    for (int l = layer_begin; l < layer_end; l++) { c->layer_pending[l] = 1; c->layer_issued[l] = 0; }
+    for (int l = layer_begin; l < layer_end; l++) { c->layer_pending[l] = 1; c->layer_issued[l] = 0; c->chunk_blocks[l] = 0; c->n_chunks[l] = 0; }
     c->l3_status = CALVO_OK;
     c->l3_err.clear();
   }
@@ -735,6 +827,14 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   std::vector<Tile> tiles;
   std::vector<WorkItem> items;
   std::vector<int32_t> split_tiles;
+  std::vector<std::vector<int32_t>> groups;     // chunk-granular launches: work item indices per launch
+  int cb = 0, nck = 0;
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    cb = c->chunk_blocks[layer];
+    nck = c->n_chunks[layer];
+  }
+  const bool chunked = mfma && cb > 0 && attn_mfma_splits_context() && !c->force_splits;
   if (mfma) {
     for (int r = 0; r < n_reqs; r++) {
       const int nt = (reqs[r].suffix_len + tile_tokens - 1) / tile_tokens;
@@ -758,7 +858,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
       return len;
     };
     int want = 1;
-    if (attn_mfma_splits_context()) {
+    if (attn_mfma_splits_context() && !chunked) {
       if (c->force_splits) want = c->force_splits;
       else if (wgs > 0 && wgs <= 16 * (int64_t)c->n_cus) {
         // Choose the number of pieces by replaying the launch: workgroups start in grid order on
@@ -807,13 +907,39 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
         }
       }
     }
-    for (const Tile& t : tiles) {
-      const int len = piece_len(t.n_sub, want);
-      const int n = (t.n_sub + len - 1) / len;
-      const int32_t first = (int32_t)items.size();
-      if (n > 1) split_tiles.push_back(first);
-      for (int k = 0; k < n; k++)
-        items.push_back({t.req, t.tile, k * len, std::min(t.n_sub, (k + 1) * len), n, first, 0, 0});
+    if (chunked) {
+      // The layer was loaded in chunks of cb block indices: piece k of every tile covers the
+      // sub-tiles of chunk k and is launched behind that chunk's event; what is left (the end of
+      // the prefix that shares a sub-tile with the suffix, the suffix itself) is the last piece
+      // and waits for the whole layer.  groups[k] lists the work items of launch k.
+      groups.assign((size_t)nck + 1, {});
+      const int sub_per_chunk = cb / 2;
+      for (const Tile& t : tiles) {
+        const int full = reqs[t.req].n_prefix_blocks / 2;          // sub-tiles wholly inside the prefix
+        const int32_t first = (int32_t)items.size();
+        int n = 0;
+        for (int a = 0; a < full; a += sub_per_chunk) n++;
+        const int cut_end = std::min(full, n * sub_per_chunk);
+        const int total = n + (cut_end < t.n_sub ? 1 : 0);
+        if (total > 1) split_tiles.push_back(first);
+        for (int k = 0; k < n; k++) {
+          groups[(size_t)std::min(k, nck)].push_back((int32_t)items.size());
+          items.push_back({t.req, t.tile, k * sub_per_chunk, std::min(full, (k + 1) * sub_per_chunk), total, first, 0, 0});
+        }
+        if (cut_end < t.n_sub) {
+          groups[(size_t)nck].push_back((int32_t)items.size());
+          items.push_back({t.req, t.tile, cut_end, t.n_sub, total, first, 0, 0});
+        }
+      }
+    } else {
+      for (const Tile& t : tiles) {
+        const int len = piece_len(t.n_sub, want);
+        const int n = (t.n_sub + len - 1) / len;
+        const int32_t first = (int32_t)items.size();
+        if (n > 1) split_tiles.push_back(first);
+        for (int k = 0; k < n; k++)
+          items.push_back({t.req, t.tile, k * len, std::min(t.n_sub, (k + 1) * len), n, first, 0, 0});
+      }
     }
   }
   const size_t items_off = blob.size();
@@ -823,6 +949,11 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   const size_t split_off = blob.size();
   blob.insert(blob.end(), split_tiles.begin(), split_tiles.end());
+  std::vector<size_t> group_off;
+  for (const auto& g : groups) {
+    group_off.push_back(blob.size());
+    blob.insert(blob.end(), g.begin(), g.end());
+  }
   const size_t tables_off = blob.size();
   for (int r = 0; r < n_reqs; r++) {
     const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
@@ -873,7 +1004,9 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
 
   rc = wait_handed_over(c, layer);          // a running L3 loader: until the layer's last chunk is queued
   if (rc != CALVO_OK) return rc;
-  if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+  // chunk-granular launches wait for their own chunk; everything else for the whole layer.  The
+  // suffix rows go to slots no load writes, so they may be stored before the layer is in.
+  if (!chunked && layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
 
   unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
   const ReqDesc* d_reqs = (const ReqDesc*)c->d_att;
@@ -896,10 +1029,22 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
   HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
   if (mfma) {
-    p.n_items = (int32_t)items.size();
     p.part_o = c->part_o;
     p.part_ml = c->part_ml;
-    HIP_TRY(launch_attn_mfma(p, c->s_compute));
+    if (chunked) {
+      for (size_t g = 0; g < groups.size(); g++) {
+        if (g < (size_t)nck) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_chunk[layer][g], 0));
+        else if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+        if (groups[g].empty()) continue;
+        p.n_items = (int32_t)groups[g].size();
+        p.item_index = c->d_att + group_off[g];
+        HIP_TRY(launch_attn_mfma(p, c->s_compute));
+      }
+      p.item_index = nullptr;
+    } else {
+      p.n_items = (int32_t)items.size();
+      HIP_TRY(launch_attn_mfma(p, c->s_compute));
+    }
     HIP_TRY(launch_merge_splits(p, c->d_att + split_off, (int)split_tiles.size(), c->s_compute));
   } else {
     p.n_items = n_reqs;

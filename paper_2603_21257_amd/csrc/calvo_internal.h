@@ -34,6 +34,7 @@ struct AttnParams {
   const void* pool_layer;   // this layer's [pool_blocks][2][B][Hkv][D]
   const ReqDesc* reqs;
   const WorkItem* items;
+  const int32_t* item_index; // NULL, or n_items indices into items: the work items of this launch
   const int32_t* tables;    // per request: its block table, padded with copies of the last entry
   const int64_t* blk_offs;  // per request: slot * block_bytes of the even blocks, then of the odd blocks
   int32_t n_items;          // tiles over all requests

@@ -56,9 +56,10 @@ def make_requests(w: wl.Workload, host: torch.Tensor):
 
 
 def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_streams: int = 0,
-            scale: float = 0.0, append_suffix: bool = True):
+            scale: float = 0.0, append_suffix: bool = True, chunk_blocks=None):
     """Whole path on cuda:0.  Returns (pool image as stored-dtype numpy [L][slots][elems],
-    out as stored-dtype numpy [L][T][Hq][D])."""
+    out as stored-dtype numpy [L][T][Hq][D]).  chunk_blocks: per-layer chunk sizes for the
+    chunk-granular load (None: whole layers)."""
     s = w.shape
     dev = torch.device("cuda:0")
     dt = torch_dtype(s)
@@ -75,7 +76,10 @@ def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_s
                           staging_bytes=staging_bytes, n_staging=n_staging, n_copy_streams=n_copy_streams)
     try:
         reqs = make_requests(w, host)
-        cb.calvo_kv_ingest(ctx, reqs, 0, s.n_layers)
+        if chunk_blocks is None:
+            cb.calvo_kv_ingest(ctx, reqs, 0, s.n_layers)
+        else:
+            cb.calvo_kv_ingest_chunked(ctx, reqs, 0, s.n_layers, chunk_blocks)
         for l in range(s.n_layers):
             cb.calvo_prefill_attn(ctx, l, q[l] if T else None, (ks[l] if append_suffix and T else None),
                                   (vs[l] if append_suffix and T else None), out[l] if T else None,
