@@ -250,6 +250,46 @@ int calvo_sched_pick(int policy, const calvo_cost_model* model, const calvo_job*
 int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_job* jobs, int n, const double* load_s,
                          const double* comp_s, int pipelined, double* start_s, double* finish_s);
 
+/* ---- Slot allocation for the paged KV space with proactive reservation (paper Section 3.1:
+ * when a lower-level transfer is issued, the destination space one level up is requested at the same
+ * time, so a block can move on as soon as it arrives; footnote: if HBM is short this "simply degrades
+ * to the reactive allocation").  Host code only; thread safe.  A slot carries a reference count: a
+ * prefix run shared by several requests is referenced once per request and becomes free when the
+ * last one releases it.  Which free slot a call hands out is unspecified (distinct, in range, free). */
+typedef struct calvo_pool calvo_pool;
+
+/* Bookkeeping for n_blocks slots (0 < n_blocks < 2^31), all free. */
+int calvo_pool_create(int64_t n_blocks, calvo_pool** out);
+int calvo_pool_destroy(calvo_pool* pool);
+
+/* n distinct free slots -> slots[0..n) (HOST), each with one reference; all or nothing:
+ * CALVO_ENOMEM (nothing reserved) if fewer than n are free. */
+int calvo_pool_reserve(calvo_pool* pool, int32_t n, int32_t* slots);
+/* One more reference on each listed slot; all must be in use (CALVO_EINVAL, nothing changed, otherwise). */
+int calvo_pool_retain(calvo_pool* pool, const int32_t* slots, int32_t n);
+/* Drops one reference per listed entry; a slot without references becomes free.  All or nothing:
+ * CALVO_EINVAL if an entry is out of range or has no reference left. */
+int calvo_pool_release(calvo_pool* pool, const int32_t* slots, int32_t n);
+/* Any of the outputs may be NULL.  n_refs = sum of all reference counts. */
+int calvo_pool_counts(calvo_pool* pool, int64_t* n_free, int64_t* n_used, int64_t* n_refs, int64_t* n_waiting);
+
+/* Admission of a request, called when its lower-level transfer is issued (proactive allocation).
+ * The request maps n_shared slots that are already in use (a prefix run it shares; distinct) and
+ * needs n_own new ones.  If no earlier admission is waiting and n_own slots are free:
+ * table[0..n_shared+n_own) = the shared slots (one more reference each) followed by the new slots,
+ * CALVO_OK.  Otherwise (HBM short) the request joins the wait queue - reactive allocation -
+ * *ticket identifies it and the call returns CALVO_ENOTREADY; its shared slots are referenced from
+ * this moment so the run cannot be freed under it.  CALVO_ENOMEM if n_own exceeds the whole pool,
+ * CALVO_EINVAL for bad arguments (nothing changed). */
+int calvo_pool_admit(calvo_pool* pool, const int32_t* shared, int32_t n_shared, int32_t n_own, int32_t* table,
+                     int64_t* ticket);
+/* Reactive path: completes a queued admission if it is the oldest one waiting and its slots are free
+ * now (table as above, CALVO_OK), else CALVO_ENOTREADY.  Queued admissions are served strictly in
+ * arrival order.  CALVO_EINVAL for an unknown ticket. */
+int calvo_pool_retry(calvo_pool* pool, int64_t ticket, int32_t* table);
+/* Withdraws a queued admission and gives back its references on the shared run. */
+int calvo_pool_cancel(calvo_pool* pool, int64_t ticket);
+
 /* Measurement helper: duration in milliseconds of the most recent attention kernel queued by
  * calvo_prefill_attn for `layer` (HIP events recorded around the kernel on the compute
  * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */

@@ -23,7 +23,9 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
            "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_cost_fit", "calvo_cost_estimate",
-           "calvo_sched_pick", "calvo_sched_simulate", "calvo_last_error"]
+           "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
+           "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
+           "calvo_pool_cancel", "calvo_last_error"]
 CALVO_POLICY_FIFO, CALVO_POLICY_SJF, CALVO_POLICY_SJF_PT, CALVO_POLICY_LSTF, CALVO_POLICY_EDF = range(5)
 
 
@@ -96,6 +98,16 @@ def lib() -> C.CDLL:
                                        C.c_int, C.c_double, C.POINTER(C.c_int)]
         L.calvo_sched_simulate.argtypes = [C.c_int, C.POINTER(calvo_cost_model), C.POINTER(calvo_job), C.c_int, dp, dp,
                                            C.c_int, dp, dp]
+        i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+        L.calvo_pool_create.argtypes = [C.c_int64, C.POINTER(C.c_void_p)]
+        L.calvo_pool_destroy.argtypes = [C.c_void_p]
+        L.calvo_pool_reserve.argtypes = [C.c_void_p, C.c_int32, i32p]
+        L.calvo_pool_retain.argtypes = [C.c_void_p, i32p, C.c_int32]
+        L.calvo_pool_release.argtypes = [C.c_void_p, i32p, C.c_int32]
+        L.calvo_pool_counts.argtypes = [C.c_void_p, i64p, i64p, i64p, i64p]
+        L.calvo_pool_admit.argtypes = [C.c_void_p, i32p, C.c_int32, C.c_int32, i32p, i64p]
+        L.calvo_pool_retry.argtypes = [C.c_void_p, C.c_int64, i32p]
+        L.calvo_pool_cancel.argtypes = [C.c_void_p, C.c_int64]
         L.calvo_last_error.argtypes = []
         L.calvo_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -270,3 +282,70 @@ def calvo_attn_kernel_ms(ctx: int, layer: int) -> float:
     ms = C.c_float()
     _check(lib().calvo_attn_kernel_ms(ctx, layer, C.byref(ms)))
     return ms.value
+
+
+# ---- slot allocation (host code; no GPU needed)
+
+def _pool_check(rc: int, ok=(CALVO_OK,)) -> int:
+    if rc not in ok:
+        raise CalvoError(rc, "slot allocation call refused")
+    return rc
+
+
+def _i32(a):
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def calvo_pool_create(n_blocks: int) -> int:
+    out = C.c_void_p()
+    _pool_check(lib().calvo_pool_create(int(n_blocks), C.byref(out)))
+    return out.value
+
+
+def calvo_pool_destroy(pool: int) -> None:
+    _pool_check(lib().calvo_pool_destroy(pool))
+
+
+def calvo_pool_reserve(pool: int, n: int):
+    """n free slots as an int32 array, or None if fewer than n are free."""
+    arr, ap = _i32(np.zeros(max(n, 1)))
+    rc = _pool_check(lib().calvo_pool_reserve(pool, n, ap), ok=(CALVO_OK, CALVO_ENOMEM))
+    return arr[:n].copy() if rc == CALVO_OK else None
+
+
+def calvo_pool_retain(pool: int, slots) -> None:
+    arr, ap = _i32(slots)
+    _pool_check(lib().calvo_pool_retain(pool, ap, len(arr)))
+
+
+def calvo_pool_release(pool: int, slots) -> None:
+    arr, ap = _i32(slots)
+    _pool_check(lib().calvo_pool_release(pool, ap, len(arr)))
+
+
+def calvo_pool_counts(pool: int) -> dict:
+    v = [C.c_int64() for _ in range(4)]
+    _pool_check(lib().calvo_pool_counts(pool, *[C.byref(x) for x in v]))
+    return dict(zip(("free", "used", "refs", "waiting"), (x.value for x in v)))
+
+
+def calvo_pool_admit(pool: int, shared, n_own: int):
+    """(table, 0) when the slots were granted at once (proactive), (None, ticket) when the request
+    was queued for reactive allocation."""
+    sh, sp = _i32(shared)
+    table, tp = _i32(np.zeros(max(len(sh) + n_own, 1)))
+    ticket = C.c_int64()
+    rc = _pool_check(lib().calvo_pool_admit(pool, sp, len(sh), n_own, tp, C.byref(ticket)), ok=(CALVO_OK, CALVO_ENOTREADY))
+    return (table[:len(sh) + n_own].copy(), 0) if rc == CALVO_OK else (None, ticket.value)
+
+
+def calvo_pool_retry(pool: int, ticket: int, n_table: int):
+    """The table of a queued admission once it can be served, else None."""
+    table, tp = _i32(np.zeros(max(n_table, 1)))
+    rc = _pool_check(lib().calvo_pool_retry(pool, ticket, tp), ok=(CALVO_OK, CALVO_ENOTREADY))
+    return table[:n_table].copy() if rc == CALVO_OK else None
+
+
+def calvo_pool_cancel(pool: int, ticket: int) -> None:
+    _pool_check(lib().calvo_pool_cancel(pool, ticket))

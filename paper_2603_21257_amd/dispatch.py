@@ -36,3 +36,61 @@ def serve_trace(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Se
         finish[i] = clock() - t0
         done[i] = True
     return start, finish
+
+
+def serve_trace_pooled(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
+                       pool: int, n_blocks: Sequence[int], run_request: Callable[[int, "object"], None],
+                       hold_s: Sequence[float], clock: Callable[[], float] = time.perf_counter,
+                       sleep: Callable[[float], None] = time.sleep):
+    """serve_trace with the KV slots of every request taken from a calvo_pool (paper Section 3.1,
+    proactive allocation): the moment a request is picked - when its loading is issued - its
+    n_blocks[i] destination slots are requested.  If HBM has room they are granted at once; if not,
+    the request waits for slots to come back (reactive allocation) and loading starts then.  Request
+    i keeps its slots for hold_s[i] seconds after its first token (the decode phase that follows the
+    prefill) and releases them afterwards.
+
+    run_request(i, table) gets the granted slot ids (int32 array of n_blocks[i]).
+    Returns (start_s, finish_s, reactive, alloc_wait_s): reactive[i] tells whether request i had to
+    wait for slots, alloc_wait_s[i] for how long.
+    """
+    n = len(jobs)
+    done = [False] * n
+    start, finish = [0.0] * n, [0.0] * n
+    reactive, alloc_wait = [False] * n, [0.0] * n
+    holders = []                                       # (release time, table)
+    t0 = clock()
+
+    def release_expired(now):
+        for when, table in holders:
+            if when <= now:
+                cb.calvo_pool_release(pool, table)
+        holders[:] = [h for h in holders if h[0] > now]
+
+    for _ in range(n):
+        while True:
+            now = clock() - t0
+            release_expired(now)
+            i = cb.calvo_sched_pick(policy, model, jobs, done, now)
+            if i >= 0:
+                break
+            sleep(max(0.0, min(jobs[k][0] for k in range(n) if not done[k]) - now))
+        table, ticket = cb.calvo_pool_admit(pool, [], int(n_blocks[i]))
+        if table is None:                              # HBM short: reactive allocation
+            reactive[i] = True
+            while table is None:
+                if not holders:
+                    cb.calvo_pool_cancel(pool, ticket)
+                    raise RuntimeError(f"request {i} needs {n_blocks[i]} slots and nothing is left to release")
+                wake = min(h[0] for h in holders)
+                sleep(max(0.0, wake - (clock() - t0)))
+                release_expired(clock() - t0)
+                table = cb.calvo_pool_retry(pool, ticket, int(n_blocks[i]))
+            alloc_wait[i] = (clock() - t0) - now
+        start[i] = clock() - t0
+        run_request(i, table)
+        finish[i] = clock() - t0
+        done[i] = True
+        holders.append((finish[i] + float(hold_s[i]), table))
+    for _, table in holders:
+        cb.calvo_pool_release(pool, table)
+    return start, finish, reactive, alloc_wait

@@ -94,3 +94,65 @@ def test_loading_aware_sjf_lowers_average_ttft_on_the_gpu():
             cb.calvo_destroy(ctx)
     finally:
         arena.free()
+
+
+def test_requests_get_their_slots_from_the_pool_proactively_or_reactively():
+    """Three requests on a pool that cannot hold the first two at once.  Each keeps its KV slots for a
+    while after its first token (its decode phase).  R1 and R3 get their slots the moment they are
+    picked; R2 finds HBM short, waits for R1's slots to come back and is served then.  Every request's
+    attention output is checked against the oracle through the table the allocator granted."""
+    L, Hq, Hkv, D, B = 2, 8, 2, 128, 16
+    lens = [(320 * 16, 40), (352 * 16, 70), (64 * 16, 33)]
+    need = [p // B + -(-s // B) for p, s in lens]                       # 323, 357, 67 slots
+    n_pool = 440
+    assert need[0] + need[1] > n_pool >= need[1] + need[2]
+    shape = wl.Shape(L, Hq, Hkv, D, "bf16", n_pool)
+    w = wl.make_custom(wl.Shape(L, Hq, Hkv, D, "bf16", sum(need) + 4), lens, seed=4321)   # payload only; tables come from the pool
+    dev = torch.device("cuda:0")
+    pool_t = hh.to_torch(hh.sentinel_pool_np(shape), shape, dev)
+    host = hh.to_torch(w.host_kv, shape, pin=True)
+    q, ks, vs = (hh.to_torch(a, shape, dev) for a in (w.q, w.k_suffix, w.v_suffix))
+    out = torch.full((L, w.total_suffix, Hq, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    stride = w.host_blocks * shape.blk_bytes
+    ctx = cb.calvo_create(L, Hq, Hkv, D, cb.CALVO_BF16, n_pool, pool_t)
+    alloc = cb.calvo_pool_create(n_pool)
+    granted, pool_after = {}, {}
+    try:
+        def run_request(i, table):
+            assert len(table) == need[i] and len(set(table.tolist())) == need[i]
+            granted[i] = table.copy()
+            r = w.requests[i]
+            a, b = int(w.cu_suffix[i]), int(w.cu_suffix[i + 1])
+            req = cb.make_request(host.data_ptr() + r.host_block_start * shape.blk_bytes, stride, table,
+                                  r.n_prefix_blocks, r.suffix_len)
+            cb.calvo_kv_ingest(ctx, [req], 0, L)
+            for l in range(L):
+                cb.calvo_prefill_attn(ctx, l, q[l, a:b], ks[l, a:b], vs[l, a:b], out[l, a:b], [req],
+                                      np.array([0, b - a], np.int32), 0.0)
+            torch.cuda.synchronize()
+            pool_after[i] = hh.to_numpy_stored(pool_t, shape)           # this request's slots, right after its prefill
+
+        jobs = [(0.0, math.inf, p, s) for p, s in lens]
+        start, fin, reactive, waited = dispatch.serve_trace_pooled(cb.CALVO_POLICY_FIFO, None, jobs, alloc, need,
+                                                                  run_request, hold_s=[0.25, 0.05, 0.05])
+        print(f"start {start} finish {fin} reactive {reactive} waited {waited}", flush=True)
+        assert reactive == [False, True, False]
+        assert waited[1] > 0.1 and start[1] >= fin[0] + 0.2             # R2 started when R1's slots came back
+        assert cb.calvo_pool_counts(alloc) == {"free": n_pool, "used": 0, "refs": 0, "waiting": 0}
+    finally:
+        cb.calvo_pool_destroy(alloc)
+        cb.calvo_destroy(ctx)
+    out_np = hh.to_numpy_stored(out, shape)
+    for i, r in enumerate(w.requests):
+        a, b = int(w.cu_suffix[i]), int(w.cu_suffix[i + 1])
+        want_pool = np.zeros((L, n_pool, shape.blk_elems), np.uint16)
+        hh.orc.kv_ingest(want_pool, w.host_kv, granted[i], r.n_prefix_blocks, 0, r.host_block_start)
+        view = want_pool.reshape(L, n_pool, 2, B, Hkv, D)
+        for l in range(L):
+            hh.orc.suffix_append(view[l], w.k_suffix[l, a:b], w.v_suffix[l, a:b], granted[i], r.prefix_len, B)
+            want = hh.orc.prefill_attn(view[l], w.q[l, a:b], granted[i], r.prefix_len, r.suffix_len, B)
+            hh.assert_attn_close(out_np[l, a:b], want, "bf16")
+        # the granted prefix slots held exactly this request's bytes after its prefill (rows past the
+        # suffix in its last slot are undefined: a reused slot keeps its previous owner's bytes there)
+        pre = granted[i][:r.n_prefix_blocks]
+        assert np.array_equal(pool_after[i][:, pre], want_pool[:, pre])
