@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--tail-chunks", type=int, default=-1,
                     help="load each of the last --tail-layers layers in this many chunks with one readiness signal each, so "
                          "that their attention starts on the chunks that have landed (0 = whole layers only; -1 = 4 if loading "
-                         "alone takes longer than attention alone on this workload, else 0)")
+                         "alone takes longer than attention alone on this workload but less than twice as long, else 0)")
     ap.add_argument("--tail-layers", type=int, default=6)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -145,14 +145,20 @@ def main():
         nt = max(1, min(L, args.tail_layers))
         plan["chunk_blocks"] = [0] * (L - nt) + [per + (per & 1)] * nt
 
+    host_trace = []
+
     def step():
+        t0 = time.perf_counter()
         if plan["chunk_blocks"] is None:
             cb.calvo_kv_ingest(ctx, reqs, 0, L)
         else:
             cb.calvo_kv_ingest_chunked(ctx, reqs, 0, L, plan["chunk_blocks"])
+        t1 = time.perf_counter()
         for l in range(L):
             cb.calvo_prefill_attn(ctx, l, q[l], ks[l], vs[l], out[l], reqs, w.cu_suffix, 0.0)
+        t2 = time.perf_counter()
         torch.cuda.synchronize()
+        host_trace.append((t1 - t0, t2 - t1, time.perf_counter() - t2))
 
     def ingest_only():
         cb.calvo_kv_ingest(ctx, reqs, 0, L)
@@ -186,8 +192,14 @@ def main():
         t_ing = min(timed(ingest_only) for _ in range(2))
         t_att = min(timed(attn_only) for _ in range(2))
         if args.tail_chunks < 0:
-            args.tail_chunks = 4 if t_ing > t_att else 0
+            # pays when loading bounds the step and a layer's attention is a sizeable part of a layer's load
+            args.tail_chunks = 4 if t_ing > t_att >= 0.5 * t_ing else 0
         set_tail_chunks(args.tail_chunks)
+        # the interpreter's cyclic collector would otherwise run a full pass (tens of milliseconds with torch
+        # loaded) in the middle of some step's enqueue loop
+        import gc
+        gc.collect()
+        gc.disable()
         for _ in range(args.warmup):
             step()
         # ---- the timed steps
@@ -198,8 +210,11 @@ def main():
             # whole-layer launches only: the event pair of a chunk-granular layer also spans its waits
             cbs = plan["chunk_blocks"]
             kern_ms.extend(cb.calvo_attn_kernel_ms(ctx, l) for l in range(L) if not (cbs and cbs[l]))
+        gc.enable()
         ms = statistics.mean(step_ms)
         k_ms = statistics.mean(kern_ms)
+        log("[bench] host time per step, warm-up steps first (ingest call, attention calls, final wait) ms: " +
+            ", ".join("(%.2f %.2f %.2f)" % tuple(1e3 * x for x in t) for t in host_trace))
         flop_per_launch = w.attn_flop() / L
         att_tflops = flop_per_launch / (k_ms * 1e-3) / 1e12
         ing_gbps = w.ingest_bytes() / (t_ing * 1e-3) / 1e9
@@ -220,7 +235,7 @@ def main():
                        "ingest": "zero-copy kernel" if args.staging_mib == 0 else f"copy engine, {args.staging_mib} MiB staging x{args.n_staging or 2}",
                        "chunked_tail": f"{args.tail_layers} layers x {args.tail_chunks} chunks" if args.tail_chunks else "none"},
             "ttft_ms": {"mean": round(ms, 3), "median": round(statistics.median(step_ms), 3),
-                        "min": round(min(step_ms), 3), "lower_bound": round(ttft_lb, 3),
+                        "min": round(min(step_ms), 3), "each": [round(x, 3) for x in step_ms], "lower_bound": round(ttft_lb, 3),
                         "frac_of_lower_bound": round(ttft_lb / ms, 4)},
             "ingest": {"GBps": round(ing_gbps, 2), "h2d_peak_GBps": round(h2d_peak, 2),
                        "frac_of_h2d_peak": round(ing_gbps / h2d_peak, 4), "alone_ms": round(t_ing, 3),
