@@ -144,6 +144,11 @@ typedef struct {
   int32_t n_threads;   /* host threads of the L3 -> L2 copy, 1..32 (0 = 4) */
   double  l3_GBps;     /* emulated link rate in 1e9 bytes/s: a chunk of n bytes occupies the link for
                           at least n / rate; 0 = as fast as the host copies */
+  int32_t chunk_ready; /* != 0: chunk-granular readiness as in calvo_kv_ingest_chunked with chunks of
+                          chunk_bytes (an even number of blocks): the loader moves block indices
+                          [k*cb, (k+1)*cb) of every request as chunk k and records its event when it is
+                          queued for L2 -> L1; calvo_prefill_attn starts on each chunk as it lands */
+  int32_t reserved;    /* 0 */
 } calvo_l3_config;
 
 typedef struct {

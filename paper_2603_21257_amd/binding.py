@@ -42,7 +42,8 @@ class calvo_request(C.Structure):
 
 
 class calvo_l3_config(C.Structure):
-    _fields_ = [("chunk_bytes", C.c_size_t), ("n_slots", C.c_int32), ("n_threads", C.c_int32), ("l3_GBps", C.c_double)]
+    _fields_ = [("chunk_bytes", C.c_size_t), ("n_slots", C.c_int32), ("n_threads", C.c_int32), ("l3_GBps", C.c_double),
+                ("chunk_ready", C.c_int32), ("reserved", C.c_int32)]
 
 
 class calvo_l3_stats(C.Structure):
@@ -195,9 +196,10 @@ def calvo_chunk_event(ctx: int, layer: int, chunk: int, mode: int, stream=None) 
 
 
 def calvo_kv_ingest_l3(ctx: int, reqs: Sequence[calvo_request], layer_begin: int, layer_end: int,
-                       chunk_bytes: int = 0, n_slots: int = 0, n_threads: int = 0, l3_GBps: float = 0.0) -> None:
+                       chunk_bytes: int = 0, n_slots: int = 0, n_threads: int = 0, l3_GBps: float = 0.0,
+                       chunk_ready: bool = False) -> None:
     """host_kv of the requests may be pageable host memory; it must stay alive until calvo_l3_wait."""
-    cfg = calvo_l3_config(int(chunk_bytes), int(n_slots), int(n_threads), float(l3_GBps))
+    cfg = calvo_l3_config(int(chunk_bytes), int(n_slots), int(n_threads), float(l3_GBps), 1 if chunk_ready else 0, 0)
     _check(lib().calvo_kv_ingest_l3(ctx, _req_array(reqs), len(reqs), layer_begin, layer_end, C.byref(cfg)))
 
 

@@ -69,6 +69,7 @@ struct calvo_ctx {
   // request are resident
   std::vector<int32_t> chunk_blocks;
   std::vector<int32_t> n_chunks;
+  std::vector<int32_t> chunks_issued;   // chunk events recorded so far (a running loader records them one by one; guarded by mu)
   std::vector<std::vector<hipEvent_t>> ev_chunk;
   // ingest-side table copy (device) and its pinned shadow
   int32_t* d_tab_ing = nullptr;
@@ -257,6 +258,16 @@ int wait_handed_over(calvo_ctx* c, int layer) {
   return CALVO_OK;
 }
 
+// Blocks until chunk `chunk` of `layer` has been handed to the L2->L1 stage, i.e. its event has been
+// recorded (at once unless a loader is still running), or the loader failed.
+int wait_chunk_handed_over(calvo_ctx* c, int layer, int chunk) {
+  std::unique_lock<std::mutex> lk(c->mu);
+  c->cv.wait(lk, [&] { return c->chunks_issued[layer] > chunk || !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
+  if (c->chunks_issued[layer] > chunk) return CALVO_OK;
+  g_err = c->l3_err;
+  return c->l3_status != CALVO_OK ? c->l3_status : CALVO_ENOTREADY;
+}
+
 bool layer_is_issued(calvo_ctx* c, int layer) {
   std::lock_guard<std::mutex> lk(c->mu);
   return c->layer_issued[layer] != 0;
@@ -294,6 +305,7 @@ struct L3Job {
   std::vector<L3Request> reqs;
   int layer_begin = 0, layer_end = 0;
   int64_t chunk_blocks = 0;
+  bool chunk_ready = false;   // chunk-major order over block indices, one event per chunk
   int n_slots = 0, n_threads = 0;
   double rate = 0.0;          // bytes per second, 0 = unthrottled
 };
@@ -328,39 +340,63 @@ void loader_main(calvo_ctx* c, L3Job job) {
   if (e != hipSuccess) hip_fail(e, "hipSetDevice (loader)");
   auto link_free_at = clock::now();          // when the emulated link can start its next chunk
   uint64_t k = 0;
-  for (int l = job.layer_begin; l < job.layer_end && status == CALVO_OK; l++) {
+  // blocks [j0, j0 + nb) of request q, layer l (nb <= chunk_blocks): through one ring slot
+  auto move_chunk = [&](int l, const L3Request& q, int64_t j0, int64_t nb) {
     unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
-    for (size_t r = 0; r < job.reqs.size() && status == CALVO_OK; r++) {
-      const L3Request& q = job.reqs[r];
-      for (int64_t j0 = q.first; j0 < q.nblk && status == CALVO_OK; j0 += job.chunk_blocks, k++) {
-        const int64_t nb = std::min<int64_t>(job.chunk_blocks, q.nblk - j0);
-        const size_t bytes = (size_t)nb * c->blk_bytes;
-        const int slot = (int)(k % (uint64_t)job.n_slots);
-        auto t0 = clock::now();
-        if (c->l2_free_recorded[slot] && (e = hipEventSynchronize(c->ev_l2_free[slot])) != hipSuccess) {
-          hip_fail(e, "hipEventSynchronize (L2 ring slot)");
-          break;
+    const size_t bytes = (size_t)nb * c->blk_bytes;
+    const int slot = (int)(k % (uint64_t)job.n_slots);
+    k++;
+    auto t0 = clock::now();
+    if (c->l2_free_recorded[slot] && (e = hipEventSynchronize(c->ev_l2_free[slot])) != hipSuccess) {
+      hip_fail(e, "hipEventSynchronize (L2 ring slot)");
+      return;
+    }
+    auto t1 = clock::now();
+    const double waited = std::chrono::duration<double>(t1 - t0).count();
+    st.ring_wait_s += waited;
+    // The emulated link streams on its own: the time this thread spends handing a chunk to the
+    // next stage does not hold it up.  It starts the next chunk when it is free, unless it had
+    // to wait for a ring slot (back-pressure from L2 -> L1), in which case it starts now.
+    const auto start = waited > 50e-6 ? std::max(t1, link_free_at) : link_free_at;
+    parallel_copy((unsigned char*)c->l2_ring[slot],
+                  q.src + (int64_t)l * q.layer_stride + j0 * (int64_t)c->blk_bytes, bytes, job.n_threads);
+    if (job.rate > 0.0) {
+      link_free_at = start + std::chrono::duration_cast<clock::duration>(std::chrono::duration<double>((double)bytes / job.rate));
+      std::this_thread::sleep_until(link_free_at);
+    }
+    st.l3_busy_s += std::chrono::duration<double>(clock::now() - t1).count();
+    st.bytes += (int64_t)bytes;
+    st.chunks++;
+    e = enqueue_staged(c, (const unsigned char*)c->l2_ring[slot], pool_layer, c->d_tab_ing + q.tab_off + j0, nb,
+                       c->ev_l2_free[slot]);
+    if (e != hipSuccess) { hip_fail(e, "L2 -> L1 hand-over"); return; }
+    c->l2_free_recorded[slot] = 1;
+  };
+  int64_t max_blocks = 0;
+  for (const L3Request& q : job.reqs) max_blocks = std::max(max_blocks, q.nblk);
+  for (int l = job.layer_begin; l < job.layer_end && status == CALVO_OK; l++) {
+    if (!job.chunk_ready) {
+      for (size_t r = 0; r < job.reqs.size() && status == CALVO_OK; r++) {
+        const L3Request& q = job.reqs[r];
+        for (int64_t j0 = q.first; j0 < q.nblk && status == CALVO_OK; j0 += job.chunk_blocks)
+          move_chunk(l, q, j0, std::min<int64_t>(job.chunk_blocks, q.nblk - j0));
+      }
+    } else {
+      // chunk n = block indices [n cb, (n+1) cb) of every request, signalled as soon as it is queued
+      const int64_t cb = job.chunk_blocks, nck = (max_blocks + cb - 1) / cb;
+      for (int64_t n = 0; n < nck && status == CALVO_OK; n++) {
+        for (size_t r = 0; r < job.reqs.size() && status == CALVO_OK; r++) {
+          const L3Request& q = job.reqs[r];
+          const int64_t j0 = std::max(q.first, n * cb), j1 = std::min(q.nblk, (n + 1) * cb);
+          if (j0 < j1) move_chunk(l, q, j0, j1 - j0);
         }
-        auto t1 = clock::now();
-        const double waited = std::chrono::duration<double>(t1 - t0).count();
-        st.ring_wait_s += waited;
-        // The emulated link streams on its own: the time this thread spends handing a chunk to the
-        // next stage does not hold it up.  It starts the next chunk when it is free, unless it had
-        // to wait for a ring slot (back-pressure from L2 -> L1), in which case it starts now.
-        const auto start = waited > 50e-6 ? std::max(t1, link_free_at) : link_free_at;
-        parallel_copy((unsigned char*)c->l2_ring[slot],
-                      q.src + (int64_t)l * q.layer_stride + j0 * (int64_t)c->blk_bytes, bytes, job.n_threads);
-        if (job.rate > 0.0) {
-          link_free_at = start + std::chrono::duration_cast<clock::duration>(std::chrono::duration<double>((double)bytes / job.rate));
-          std::this_thread::sleep_until(link_free_at);
+        if (status != CALVO_OK) break;
+        if ((e = hipEventRecord(c->ev_chunk[l][(size_t)n], c->s_scatter)) != hipSuccess) { hip_fail(e, "hipEventRecord (chunk)"); break; }
+        {
+          std::lock_guard<std::mutex> lk(c->mu);
+          c->chunks_issued[l] = (int32_t)(n + 1);
         }
-        st.l3_busy_s += std::chrono::duration<double>(clock::now() - t1).count();
-        st.bytes += (int64_t)bytes;
-        st.chunks++;
-        e = enqueue_staged(c, (const unsigned char*)c->l2_ring[slot], pool_layer, c->d_tab_ing + q.tab_off + j0, nb,
-                           c->ev_l2_free[slot]);
-        if (e != hipSuccess) { hip_fail(e, "L2 -> L1 hand-over"); break; }
-        c->l2_free_recorded[slot] = 1;
+        c->cv.notify_all();
       }
     }
     if (status != CALVO_OK) break;
@@ -450,6 +486,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->layer_issued.assign(cfg->n_layers, 0);
   c->chunk_blocks.assign(cfg->n_layers, 0);
   c->n_chunks.assign(cfg->n_layers, 0);
+  c->chunks_issued.assign(cfg->n_layers, 0);
   c->ev_chunk.resize(cfg->n_layers);
   c->layer_pending.assign(cfg->n_layers, 0);
   c->timed.assign(cfg->n_layers, 0);
@@ -608,6 +645,7 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
     c->layer_issued[l] = 1;
     c->chunk_blocks[l] = (int32_t)cb;
     c->n_chunks[l] = (int32_t)nck;
+    c->chunks_issued[l] = (int32_t)nck;
   }
   return CALVO_OK;
 }
@@ -641,6 +679,16 @@ int calvo_chunk_event(calvo_ctx* c, int layer, int chunk, int mode, void* stream
     nck = c->n_chunks[layer];
   }
   if (chunk < 0 || chunk >= nck) return fail(CALVO_EINVAL, "chunk %d outside [0, %d) of layer %d", chunk, nck, layer);
+  if (mode == CALVO_EV_QUERY) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->chunks_issued[layer] <= chunk) {              // a running loader has not reached it yet
+      if (c->l3_status != CALVO_OK) { g_err = c->l3_err; return c->l3_status; }
+      return fail(CALVO_ENOTREADY, "chunk %d of layer %d is still loading", chunk, layer);
+    }
+  } else {
+    const int rc = wait_chunk_handed_over(c, layer, chunk);
+    if (rc != CALVO_OK) return rc;
+  }
   hipEvent_t ev = c->ev_chunk[layer][chunk];
   if (mode == CALVO_EV_QUERY) {
     hipError_t e = hipEventQuery(ev);
@@ -687,6 +735,13 @@ int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
   job.rate = cfg.l3_GBps * 1e9;
   const int64_t want = cfg.chunk_bytes ? (int64_t)(cfg.chunk_bytes / c->blk_bytes) : c->staging_blocks;
   job.chunk_blocks = std::min<int64_t>(want, c->staging_blocks);
+  job.chunk_ready = cfg.chunk_ready != 0;
+  int64_t max_blocks = 0;
+  for (int r = 0; r < n_reqs; r++) max_blocks = std::max<int64_t>(max_blocks, reqs[r].n_prefix_blocks);
+  if (job.chunk_ready) {
+    job.chunk_blocks &= ~(int64_t)1;                    // attention walks the context two blocks at a time
+    if (job.chunk_blocks < 2) return fail(CALVO_EINVAL, "l3: chunk-granular readiness needs chunks of at least two blocks");
+  }
   for (int r = 0; r < n_reqs; r++)
     if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block)
       job.reqs.push_back({src[r], reqs[r].host_layer_stride, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks, tab_off[r]});
@@ -708,9 +763,22 @@ int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
     }
     c->l2_slot_bytes = slot_bytes;
   }
+  const int64_t nck_l3 = job.chunk_ready ? (max_blocks + job.chunk_blocks - 1) / job.chunk_blocks : 0;
+  for (int l = layer_begin; l < layer_end; l++)
+    while ((int64_t)c->ev_chunk[l].size() < nck_l3) {         // the loader records them, this thread makes them
+      hipEvent_t ev = nullptr;
+      HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+      c->ev_chunk[l].push_back(ev);
+    }
   {
     std::lock_guard<std::mutex> lk(c->mu);
-    for (int l = layer_begin; l < layer_end; l++) { c->layer_pending[l] = 1; c->layer_issued[l] = 0; c->chunk_blocks[l] = 0; c->n_chunks[l] = 0; }
+    for (int l = layer_begin; l < layer_end; l++) {
+      c->layer_pending[l] = 1;
+      c->layer_issued[l] = 0;
+      c->chunk_blocks[l] = job.chunk_ready ? (int32_t)job.chunk_blocks : 0;
+      c->n_chunks[l] = (int32_t)nck_l3;
+      c->chunks_issued[l] = 0;
+    }
     c->l3_status = CALVO_OK;
     c->l3_err.clear();
   }
@@ -1002,8 +1070,10 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     c->att_pending = true;
   }
 
-  rc = wait_handed_over(c, layer);          // a running L3 loader: until the layer's last chunk is queued
-  if (rc != CALVO_OK) return rc;
+  if (!chunked) {
+    rc = wait_handed_over(c, layer);        // a running L3 loader: until the layer's last chunk is queued
+    if (rc != CALVO_OK) return rc;
+  }
   // chunk-granular launches wait for their own chunk; everything else for the whole layer.  The
   // suffix rows go to slots no load writes, so they may be stored before the layer is in.
   if (!chunked && layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
@@ -1033,8 +1103,14 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     p.part_ml = c->part_ml;
     if (chunked) {
       for (size_t g = 0; g < groups.size(); g++) {
-        if (g < (size_t)nck) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_chunk[layer][g], 0));
-        else if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+        // a device-side wait needs a recorded event: with a loader running, this thread follows it chunk by chunk
+        if (g < (size_t)nck) {
+          if ((rc = wait_chunk_handed_over(c, layer, (int)g)) != CALVO_OK) return rc;
+          HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_chunk[layer][g], 0));
+        } else {
+          if ((rc = wait_handed_over(c, layer)) != CALVO_OK) return rc;
+          if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+        }
         if (groups[g].empty()) continue;
         p.n_items = (int32_t)groups[g].size();
         p.item_index = c->d_att + group_off[g];

@@ -35,9 +35,9 @@ def test_struct_layouts_match_header_order():
         "host_kv", "host_layer_stride", "block_table", "n_prefix_blocks", "first_ingest_block", "suffix_len"]
     assert ctypes.sizeof(cb.calvo_config) == 64
     assert ctypes.sizeof(cb.calvo_request) == 40
-    assert [f[0] for f in cb.calvo_l3_config._fields_] == ["chunk_bytes", "n_slots", "n_threads", "l3_GBps"]
+    assert [f[0] for f in cb.calvo_l3_config._fields_] == ["chunk_bytes", "n_slots", "n_threads", "l3_GBps", "chunk_ready", "reserved"]
     assert [f[0] for f in cb.calvo_l3_stats._fields_] == ["bytes", "chunks", "l3_busy_s", "ring_wait_s", "total_s"]
-    assert ctypes.sizeof(cb.calvo_l3_config) == 24
+    assert ctypes.sizeof(cb.calvo_l3_config) == 32
     assert ctypes.sizeof(cb.calvo_l3_stats) == 40
 
 

@@ -129,3 +129,49 @@ def test_l3_call_rejects_bad_arguments_and_zero_copy_contexts():
     finally:
         cb.calvo_destroy(ctx0)
         cb.calvo_destroy(ctx1)
+
+
+@pytest.mark.parametrize("chunk_blocks", [2, 6, 12])
+def test_three_stage_with_chunk_granular_readiness(chunk_blocks):
+    """The loader signals every chunk of block indices as it hands it to the L2 -> L1 stage and
+    attention follows chunk by chunk (queued while the loader is still working): same bytes, same
+    attention result; a batch with a shared run, an odd block count and a request without prefix."""
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 160)
+    w = wl.make_custom(shape, [(33 * 16, 50), (9 * 16, 20), (48 * 16, 70)], seed=78, shared_blocks=5)
+    print(f"[case] three-stage chunk-ready chunk_blocks={chunk_blocks}", flush=True)
+    pool_g, out_g, st = run_l3(w, staging_bytes=16 * shape.blk_bytes, chunk_bytes=chunk_blocks * shape.blk_bytes,
+                               n_slots=3, n_threads=2, chunk_ready=True, l3_GBps=2.0)
+    pool_o, out_o = hh.run_oracle(w)
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    hh.assert_attn_close(out_g, out_o, "bf16")
+    assert st["bytes"] == w.ingest_bytes()
+
+
+def test_chunk_signals_follow_the_loader():
+    """1 layer x 48 MiB in 8 MiB chunks at an emulated 1 GB/s: early chunks report ready while later
+    ones are still on the link, and a chunk the loader has not reached says 'not ready'."""
+    shape = wl.Shape(1, 8, 8, 128, "bf16", 800)              # 64 KiB blocks
+    w = wl.make_custom(shape, [(768 * 16, 16)], seed=6)
+    s = w.shape
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(s), s, dev)
+    remote = hh.to_torch(w.host_kv, s)
+    ctx = cb.calvo_create(1, 8, 8, 128, cb.CALVO_BF16, 800, pool, staging_bytes=8 << 20)
+    try:
+        reqs = hh.make_requests(w, remote)
+        t0 = time.perf_counter()
+        cb.calvo_kv_ingest_l3(ctx, reqs, 0, 1, chunk_bytes=8 << 20, l3_GBps=1.0, chunk_ready=True)
+        assert cb.calvo_chunk_count(ctx, 0) == 6
+        assert not cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_QUERY)        # 48 ms away
+        assert cb.calvo_chunk_event(ctx, 0, 1, cb.CALVO_EV_HOST_WAIT)
+        t1 = time.perf_counter() - t0
+        assert 0.014 < t1 < 0.040, t1                                        # two chunks of 8 ms each on the link
+        assert not cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_QUERY)
+        assert not cb.calvo_layer_event(ctx, 0, cb.CALVO_EV_QUERY)
+        assert cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_HOST_WAIT)
+        assert time.perf_counter() - t0 > 0.046
+        cb.calvo_l3_wait(ctx)
+        assert cb.calvo_layer_event(ctx, 0, cb.CALVO_EV_HOST_WAIT)
+    finally:
+        cb.calvo_destroy(ctx)
+    hh.assert_pool_bit_exact(hh.to_numpy_stored(pool, s), hh.sentinel_pool_after_ingest(w))
