@@ -327,23 +327,40 @@ __global__ void __launch_bounds__(64 * NW, (NT > 1) ? 1 : 2) attn_mfma_kernel(At
   }
 }
 
-// Kernel choice.  Variant 3 (default): the software-pipelined kernel of attn_pipe.hip.  The
-// unpipelined kernel of this file stays available for comparison runs through the environment
-// variable CALVO_ATTN_VARIANT: 0 = 4 waves x 32 rows, two workgroups per CU; 1 = 4 waves x 64
-// rows (half the LDS operand traffic, one wave per SIMD); 2 = 8 waves x 32 rows.
-static int attn_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("CALVO_ATTN_VARIANT");
-    v = (e && e[0] >= '0' && e[0] <= '3') ? e[0] - '0' : 3;
-  }
-  return v;
+// Kernel choice.  Two pipelined kernels serve by default: variant 3, one 8-wave workgroup per CU
+// with 64-token tiles (attn_pipe.hip), and variant 4, two independent 4-wave workgroups per CU with
+// 32-token tiles (attn_duo.hip).  On long suffixes they run within 2 % of each other (the chip is
+// power limited: what one gains in cycles it loses in clock) and variant 3 has half the K/V traffic
+// into LDS; on short suffixes - 28 or 61 query tokens leave half of a 64-token tile empty -
+// variant 4 wastes no waves.  attn_mfma_choose picks per call.  The environment variable
+// CALVO_ATTN_VARIANT forces one: 3, 4, or the unpipelined kernel of this file for comparison runs
+// (0 = 4 waves x 32 rows, two workgroups per CU; 1 = 4 waves x 64 rows, one wave per SIMD; 2 = 8
+// waves x 32 rows).
+static int forced_variant() {
+  const char* e = getenv("CALVO_ATTN_VARIANT");      // read per call: tests switch it inside one process
+  return (e && e[0] >= '0' && e[0] <= '4') ? e[0] - '0' : -1;
 }
 
-bool attn_mfma_splits_context() { return attn_variant() == 3; }
+int attn_mfma_choose(const int32_t* suffix_lens, int n_reqs, int heads_per_wg) {
+  const int f = forced_variant();
+  if (f >= 0) return f;
+  // query rows the tiles of each kernel would hold, empty ones included
+  const int t3 = attn_pipe_tile_tokens(heads_per_wg), t4 = attn_duo_tile_tokens(heads_per_wg);
+  int64_t rows3 = 0, rows4 = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    rows3 += (int64_t)((suffix_lens[r] + t3 - 1) / t3) * t3;
+    rows4 += (int64_t)((suffix_lens[r] + t4 - 1) / t4) * t4;
+  }
+  return rows3 * 9 > rows4 * 10 ? 4 : 3;       // the larger tiles would carry over 10 % more rows
+}
 
-int attn_mfma_tile_tokens(int heads_per_wg) {
-  const int v = attn_variant();
+bool attn_mfma_splits_context(int variant) { return variant >= 3; }
+
+int attn_mfma_waves_per_wg(int variant) { return (variant == 3 || variant == 2) ? 8 : 4; }
+
+int attn_mfma_tile_tokens(int variant, int heads_per_wg) {
+  const int v = variant;
+  if (v == 4) return attn_duo_tile_tokens(heads_per_wg);
   if (v == 3) return attn_pipe_tile_tokens(heads_per_wg);
   return v == 1 ? 64 * (4 / heads_per_wg) : v == 2 ? 32 * (8 / heads_per_wg) : 32 * (4 / heads_per_wg);
 }
@@ -362,9 +379,10 @@ static hipError_t launch_variant(const AttnParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_attn_mfma(int variant, const AttnParams& p, hipStream_t stream) {
   if (p.n_items <= 0) return hipSuccess;
-  const int v = attn_variant();
+  const int v = variant;
+  if (v == 4) return launch_attn_duo(p, stream);
   if (v == 3) return launch_attn_pipe(p, stream);
   return v == 1 ? launch_variant<2, 4>(p, stream) : v == 2 ? launch_variant<1, 8>(p, stream)
                                                           : launch_variant<1, 4>(p, stream);

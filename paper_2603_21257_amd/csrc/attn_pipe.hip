@@ -660,10 +660,10 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 // Combines the pieces of split tiles: for every row and head, with m = max_c m_c,
 //     O = sum_c 2^(c2 (m_c - m)) O_c  /  sum_c 2^(c2 (m_c - m)) l_c
 // (the pieces' O_c, l_c are sums of weights 2^(c2 (score - m_c))).  One workgroup of 256 threads per
-// (split tile, head group, wave slot): thread = (row 0..31, 16-float chunk 0..7).  A piece in which
+// (split tile, head group, wave slot of the attention workgroup): thread = (row 0..31, 16-float chunk 0..7).  A piece in which
 // a row saw no key has l_c = 0 and m_c = -inf and drops out.
 __global__ void __launch_bounds__(256) merge_splits_kernel(AttnParams p, const int32_t* split_tiles) {
-  constexpr int NW = 8;
+  const int NW = p.waves_per_wg;
   const int HW = p.heads_per_wg, NHG = p.n_q_heads / HW, TPW = NW / HW;
   const int wave_slot = blockIdx.x % NW;
   const int hg = (blockIdx.x / NW) % NHG;
@@ -733,7 +733,7 @@ hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_merge_splits(const AttnParams& p, const int32_t* split_tiles, int n_split_tiles, hipStream_t stream) {
   if (n_split_tiles <= 0) return hipSuccess;
-  const unsigned grid = (unsigned)n_split_tiles * (unsigned)(p.n_q_heads / p.heads_per_wg) * 8u;
+  const unsigned grid = (unsigned)n_split_tiles * (unsigned)(p.n_q_heads / p.heads_per_wg) * (unsigned)p.waves_per_wg;
   hipLaunchKernelGGL(pipe::merge_splits_kernel, dim3(grid), dim3(256), 0, stream, p, split_tiles);
   return hipGetLastError();
 }

@@ -866,7 +866,13 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const int G = cf.n_q_heads / cf.n_kv_heads;
   const bool mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
   const int HW = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  const int tile_tokens = mfma ? attn_mfma_tile_tokens(HW) : 1;
+  int variant = 0;
+  if (mfma) {
+    std::vector<int32_t> slens(n_reqs);
+    for (int r = 0; r < n_reqs; r++) slens[r] = reqs[r].suffix_len;
+    variant = attn_mfma_choose(slens.data(), n_reqs, HW);
+  }
+  const int tile_tokens = mfma ? attn_mfma_tile_tokens(variant, HW) : 1;
 
   // ---- descriptor blob: requests, work items (heaviest first), block tables, block byte offsets.
   // Each request's table is followed by copies of its last entry (kTablePad of them, one more if
@@ -902,7 +908,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     cb = c->chunk_blocks[layer];
     nck = c->n_chunks[layer];
   }
-  const bool chunked = mfma && cb > 0 && attn_mfma_splits_context() && !c->force_splits;
+  const bool chunked = mfma && cb > 0 && attn_mfma_splits_context(variant) && !c->force_splits;
   if (mfma) {
     for (int r = 0; r < n_reqs; r++) {
       const int nt = (reqs[r].suffix_len + tile_tokens - 1) / tile_tokens;
@@ -925,18 +931,20 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
       if (n > 1 && !c->force_splits) len = (len + 5) / 8 * 8 + 2;
       return len;
     };
+    const int64_t wg_slots = (int64_t)c->n_cus * (8 / attn_mfma_waves_per_wg(variant));   // workgroups resident at a time
     int want = 1;
-    if (attn_mfma_splits_context() && !chunked) {
+    if (attn_mfma_splits_context(variant) && !chunked) {
       if (c->force_splits) want = c->force_splits;
-      else if (wgs > 0 && wgs <= 16 * (int64_t)c->n_cus) {
+      else if (wgs > 0 && wgs <= 16 * wg_slots) {
         // Choose the number of pieces by replaying the launch: workgroups start in grid order on
-        // the first free CU (one workgroup per CU), a piece costs its sub-tiles plus a fixed
+        // the first free workgroup slot (one or two per CU), a piece costs its sub-tiles plus a fixed
         // pipeline fill and drain, cut tiles pay the merge.  This covers both too few workgroups
         // for the chip and a workgroup count just above a whole number of rounds (640 equal
         // workgroups on 256 CUs take three rounds; cut in two they take five half-length rounds).
         // The decision depends only on the batch's lengths and is kept for the following layers.
         std::vector<int64_t> key;
         key.reserve(2 * n_reqs);
+        key.push_back(variant);
         for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
         if (key == c->plan_key) want = c->plan_want;
         else {
@@ -944,8 +952,8 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
           double best = 0;
           std::vector<int64_t> heap;
           for (int n : cands) {
-            if (n > 1 && wgs * n > 16 * (int64_t)c->n_cus) break;
-            heap.assign((size_t)c->n_cus, 0);            // min-heap of the times at which CUs become free
+            if (n > 1 && wgs * n > 16 * wg_slots) break;
+            heap.assign((size_t)wg_slots, 0);            // min-heap of the times at which workgroup slots become free
             auto cmp = std::greater<int64_t>();
             bool cut = false;
             int64_t end = 0;
@@ -1048,7 +1056,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   rc = ensure_att_blob(c, blob.size());
   if (rc != CALVO_OK) return rc;
   if (!split_tiles.empty()) {
-    const size_t slots = items.size() * (size_t)(cf.n_q_heads / HW) * 8;
+    const size_t slots = items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant);
     if (slots > c->part_slots) {
       HIP_TRY(hipStreamSynchronize(c->s_compute));
       if (c->part_o) (void)hipFree(c->part_o);
@@ -1096,6 +1104,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   p.blk_offs = (const int64_t*)(c->d_att + offs_off);
   p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
   p.heads_per_wg = HW; p.tile_tokens = tile_tokens;
+  p.waves_per_wg = attn_mfma_waves_per_wg(variant);
   p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
   HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
   if (mfma) {
@@ -1114,12 +1123,12 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
         if (groups[g].empty()) continue;
         p.n_items = (int32_t)groups[g].size();
         p.item_index = c->d_att + group_off[g];
-        HIP_TRY(launch_attn_mfma(p, c->s_compute));
+        HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
       }
       p.item_index = nullptr;
     } else {
       p.n_items = (int32_t)items.size();
-      HIP_TRY(launch_attn_mfma(p, c->s_compute));
+      HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
     }
     HIP_TRY(launch_merge_splits(p, c->d_att + split_off, (int)split_tiles.size(), c->s_compute));
   } else {

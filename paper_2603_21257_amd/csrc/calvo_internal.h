@@ -41,6 +41,7 @@ struct AttnParams {
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t heads_per_wg;     // MFMA kernel: 1, 2 or 4 query heads of one KV group per workgroup
   int32_t tile_tokens;      // suffix tokens per work item
+  int32_t waves_per_wg;     // waves of an attention workgroup (8 or 4): layout of the split-KV partials
   float scale;              // softmax scale (natural-exponent units)
   // split-KV partial results, used by work items with n_splits > 1: per work item, head group, wave
   // (head of the group x 32-token half of the tile): part_o [32 rows][D] fp32 unnormalised,
@@ -66,10 +67,15 @@ hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_
                                  int32_t blk_bytes, int grid, hipStream_t stream);
 hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
-hipError_t launch_attn_mfma(const AttnParams& p, hipStream_t stream);
-int attn_mfma_tile_tokens(int heads_per_wg);
-bool attn_mfma_splits_context();   // whether the selected MFMA kernel handles work items with n_splits > 1
+// which MFMA kernel serves a batch with these suffix lengths (see attn_mfma.hip); the other calls take its answer
+int attn_mfma_choose(const int32_t* suffix_lens, int n_reqs, int heads_per_wg);
+hipError_t launch_attn_mfma(int variant, const AttnParams& p, hipStream_t stream);
+int attn_mfma_tile_tokens(int variant, int heads_per_wg);
+bool attn_mfma_splits_context(int variant);   // whether that kernel handles work items with n_splits > 1
 hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
+hipError_t launch_attn_duo(const AttnParams& p, hipStream_t stream);
+int attn_duo_tile_tokens(int heads_per_wg);
+int attn_mfma_waves_per_wg(int variant);
 // combines the pieces of every split tile into out (bf16); n_split_tiles entries in split_tiles =
 // indices of the first work item of each split tile
 hipError_t launch_merge_splits(const AttnParams& p, const int32_t* split_tiles, int n_split_tiles, hipStream_t stream);

@@ -84,6 +84,23 @@ def test_bf16_forced_context_splits(n_splits, monkeypatch):
     check(w)
 
 
+@pytest.mark.parametrize("variant", [3, 4])
+def test_bf16_both_pipelined_kernels_on_the_same_batches(variant, monkeypatch):
+    """The library picks one of two pipelined kernels per call (8-wave workgroups with 64-token tiles,
+    or two 4-wave workgroups per CU with 32-token tiles); here each is forced on batches the other
+    would have served: ragged suffixes, a forced split, group sizes 1 and 2, chunk-granular loading."""
+    monkeypatch.setenv("CALVO_ATTN_VARIANT", str(variant))
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 400)
+    check(wl.make_custom(shape, [(1024, 200), (48, 77), (0, 130), (2048, 28), (512, 64)], seed=2000 + variant))
+    check(wl.make_custom(wl.Shape(1, 10, 2, 128, "bf16", 300), [(96 * 16, 300)], seed=2010 + variant))
+    check(wl.make_custom(wl.Shape(1, 4, 2, 128, "bf16", 300), [(64 * 16, 150), (32 * 16, 31)], seed=2020 + variant))
+    check(wl.make_custom(wl.Shape(2, 8, 2, 128, "bf16", 600), [(8192, 40)], seed=2030 + variant))   # automatic split-KV
+    pool_g, out_g = hh.run_hip(wl.make_custom(shape, [(63 * 16, 77)], seed=2040), chunk_blocks=[6, 16])
+    pool_o, out_o = hh.run_oracle(wl.make_custom(shape, [(63 * 16, 77)], seed=2040))
+    hh.assert_pool_bit_exact(pool_g, pool_o)
+    hh.assert_attn_close(out_g, out_o, "bf16")
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2), (6, 2), (12, 4)])
 def test_bf16_mfma_gqa_group_sizes(Hq, Hkv):
     shape = wl.Shape(1, Hq, Hkv, 128, "bf16", 64)
