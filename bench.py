@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
 # HBM bytes of one attention launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in
 # profiles/attn_pipe_kernel_cfg3.md (calibrated against the scatter kernel, a plain copy of known size).
 # Counters cannot be read from inside this process, so the figure is carried over from that profile.
-PROFILED_HBM_BYTES_PER_LAUNCH = {3: 651.8e6}
+PROFILED_HBM_BYTES_PER_LAUNCH = {3: 654.2e6}      # attn_pipe_kernel on workload 3
 
 
 def log(*a):
@@ -213,6 +213,7 @@ def main():
             cbs = plan["chunk_blocks"]
             kern_ms.extend(cb.calvo_attn_kernel_ms(ctx, l) for l in range(L) if not (cbs and cbs[l]))
         gc.enable()
+        kernel_id, kernel_wgs = cb.calvo_attn_kernel_info(ctx, 0)
         ms = statistics.mean(step_ms)
         k_ms = statistics.mean(kern_ms)
         log("[bench] host time per step, warm-up steps first (ingest call, attention calls, final wait) ms: " +
@@ -247,8 +248,9 @@ def main():
             "overlap": round(overlap, 4),
             "roofline": {"bound": "mfma", "achieved": round(att_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "traffic": PROFILED_HBM_BYTES_PER_LAUNCH.get(args.config),
-                         "kernel": "calvo::pipe::attn_pipe_kernel", "flop_per_launch": flop_per_launch,
+                         "traffic": PROFILED_HBM_BYTES_PER_LAUNCH.get(args.config) if kernel_id == 3 and not args.custom else None,
+                         "kernel": cb.ATTN_KERNEL_NAMES.get(kernel_id, f"calvo::attn_mfma_kernel (variant {kernel_id})"),
+                         "workgroups_per_launch": kernel_wgs, "flop_per_launch": flop_per_launch,
                          "avg_launch_ms": round(k_ms, 4)},
         }
         if not args.no_three_stage and w.ingest_bytes() <= (16 << 30):

@@ -300,6 +300,13 @@ int calvo_pool_cancel(calvo_pool* pool, int64_t ticket);
  * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */
 int calvo_attn_kernel_ms(calvo_ctx* ctx, int layer, float* ms);
 
+/* Measurement helper: which attention kernel the most recent calvo_prefill_attn for `layer` chose
+ * (*kernel: 3 = 8-wave workgroups with 64-token tiles, 4 = two 4-wave workgroups per CU with 32-token
+ * tiles, 0-2 = comparison variants, -1 = the vector-ALU kernel for fp32 pools / other head dims) and
+ * how many workgroups its work items made (*n_workgroups; 0 for the vector-ALU kernel).  Either
+ * output may be NULL.  CALVO_ENOTREADY if none was queued. */
+int calvo_attn_kernel_info(calvo_ctx* ctx, int layer, int* kernel, int* n_workgroups);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* calvo_last_error(void);
 

@@ -22,7 +22,7 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
            "calvo_pool_cancel", "calvo_last_error"]
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
+        L.calvo_attn_kernel_info.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         dp = C.POINTER(C.c_double)
         L.calvo_cost_fit.argtypes = [dp, dp, C.c_int, dp, dp]
         L.calvo_cost_estimate.argtypes = [C.POINTER(calvo_cost_model), C.POINTER(calvo_job), dp, dp]
@@ -278,6 +279,16 @@ def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pip
     _sched_check(lib().calvo_sched_simulate(policy, C.byref(m) if m is not None else None, _job_array(jobs), n, la[1], ca[1],
                                             1 if pipelined else 0, sp, fp))
     return start[:n], fin[:n]
+
+
+ATTN_KERNEL_NAMES = {3: "calvo::pipe::attn_pipe_kernel", 4: "calvo::duo::attn_duo_kernel", -1: "calvo::attn_simple_kernel"}
+
+
+def calvo_attn_kernel_info(ctx: int, layer: int):
+    """(kernel id, number of workgroups) of the layer's most recent attention launch."""
+    k, n = C.c_int(), C.c_int()
+    _check(lib().calvo_attn_kernel_info(ctx, layer, C.byref(k), C.byref(n)))
+    return k.value, n.value
 
 
 def calvo_attn_kernel_ms(ctx: int, layer: int) -> float:

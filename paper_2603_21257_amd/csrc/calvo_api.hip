@@ -86,6 +86,7 @@ struct calvo_ctx {
   bool att_pending = false;
   std::vector<hipEvent_t> ev_t0, ev_t1;
   std::vector<char> timed;
+  std::vector<int32_t> last_variant, last_wgs;   // per layer: attention kernel chosen, workgroups launched
   int scatter_grid = 64;
   int force_splits = 0;           // CALVO_ATTN_SPLITS: pieces per tile (0 = automatic)
   int split_min = 48;             // shortest piece of a cut tile, in 32-key sub-tiles
@@ -490,6 +491,8 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   c->ev_chunk.resize(cfg->n_layers);
   c->layer_pending.assign(cfg->n_layers, 0);
   c->timed.assign(cfg->n_layers, 0);
+  c->last_variant.assign(cfg->n_layers, -1);
+  c->last_wgs.assign(cfg->n_layers, 0);
   for (int l = 0; l < cfg->n_layers; l++) {
     CREATE_TRY(hipEventCreateWithFlags(&c->ev_layer[l], hipEventDisableTiming));
     CREATE_TRY(hipEventCreate(&c->ev_t0[l]));
@@ -1137,6 +1140,17 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   HIP_TRY(hipEventRecord(c->ev_t1[layer], c->s_compute));
   c->timed[layer] = 1;
+  c->last_variant[layer] = mfma ? variant : -1;
+  c->last_wgs[layer] = mfma ? (int32_t)(items.size() * (size_t)(cf.n_q_heads / HW)) : 0;
+  return CALVO_OK;
+}
+
+int calvo_attn_kernel_info(calvo_ctx* c, int layer, int* kernel, int* n_workgroups) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  if (!c->timed[layer]) return fail(CALVO_ENOTREADY, "no attention kernel was queued for layer %d", layer);
+  if (kernel) *kernel = c->last_variant[layer];
+  if (n_workgroups) *n_workgroups = c->last_wgs[layer];
   return CALVO_OK;
 }
 

@@ -1,4 +1,4 @@
-// Microbenchmark: how the two instruction streams of the pipelined attention kernel share one
+// Microbenchmark: how the two instruction streams of the pipelined attention kernels share one
 // SIMD of gfx950.  Stream M = bursts of 16 LDS-fed v_mfma_f32_32x32x16_bf16 (the QK/PV half of
 // a step, operands read four MFMAs ahead with the kernel's swizzled addresses); stream S = the
 // 32-key softmax of a step (16 fused multiply-adds, 16 v_exp_f32, 8 bf16 packs, 8 v_dot2 row
@@ -6,7 +6,15 @@
 // s_memtime.  Not part of the library; build and run by hand:
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops \
 //         paper_2603_21257_amd/csrc/probe_coissue.hip -o probe_coissue && ./probe_coissue
+// Compile-time variants:
+//   -DPRIO=1 / -DPRIO=2   raise the wave priority (s_setprio 3) around the softmax / around the MFMA burst
+//   -DM16                 the burst uses 32 v_mfma_f32_16x16x32_bf16 instead of 16 of the 32x32x16 shape
+//   -DLEAN                the softmax adds its row sum straight into the running sum (one dependent chain)
+// The "fused" runs interleave the softmax instructions between the MFMAs of the same wave.
 #include <hip/hip_runtime.h>
+#ifndef PRIO
+#define PRIO 0
+#endif
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -26,9 +34,10 @@ __device__ inline bf16x8 rdtr(const lds_u8* a) {
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 constexpr int PD = 4;
-enum Role { IDLE = 0, MFMA = 1, SOFTMAX = 2, ALTERNATE = 3 };
+enum Role { IDLE = 0, MFMA = 1, SOFTMAX = 2, ALTERNATE = 3, FUSED = 4 };
 // sync (ALTERNATE only): 0 no barrier, 1 one barrier per step, 2 one per half step
-__global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int iters, int roleA, int roleB, int sync) {
+template <int NVT>
+__global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int iters, int roleA, int roleB, int sync, int nvsel) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const lds_u8* lds = (const lds_u8*)smem;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -45,7 +54,7 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
   const lds_u8* ka_addr[8]; const lds_u8* va_addr[4];
   for (int ks = 0; ks < 8; ks++) ka_addr[ks] = lds + ln * 256 + (((2 * ks + lh) ^ (ln & 15)) << 4);
   for (int dt = 0; dt < 4; dt++) va_addr[dt] = lds + 65536 + v_row * 256 + ((4 * (dt ^ (v_row & 3)) + v_c0) << 4) + (s16 & 1) * 8;
-  float m_run = 0.5f, l_run = 0.f; const float c2 = 0.1275f;
+  float m_run = 0.5f, l_run = 0.f; const float c2 = 0.1275f; float nmc = -m_run * c2;
   bf16x2 ones; ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
   bf16x8 pre[PD];
   auto operand = [&](auto idx, int slot) -> bf16x8 {
@@ -55,6 +64,34 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
   };
   auto prefetch = [&](int slot) { static_for<0, PD>([&](auto idx) { pre[decltype(idx)::value] = operand(idx, slot); }); };
   // 16 MFMAs on the operands of `slot`; stream == true also requests the first operands of `next`
+#ifdef M16
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  f32x4 o16[16]; for (int d = 0; d < 16; d++) for (int r = 0; r < 4; r++) o16[d][r] = 0.f;
+  auto burst = [&](int slot, int next, bool stream) {
+    bf16x8 opnd[16];
+    static_for<0, PD>([&](auto idx) { opnd[decltype(idx)::value] = pre[decltype(idx)::value]; });
+    f32x4 sn4[4]; for (int d = 0; d < 4; d++) for (int r = 0; r < 4; r++) sn4[d][r] = 0.f;
+    static_for<0, 16>([&](auto idx) {
+      constexpr int i = decltype(idx)::value, k = i >> 1;
+      if constexpr (i & 1) {
+        o16[(2 * k) & 15] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], pb[0], o16[(2 * k) & 15], 0, 0, 0);
+        o16[(2 * k + 1) & 15] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], pb[1], o16[(2 * k + 1) & 15], 0, 0, 0);
+      } else {
+        sn4[k & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], qB[k], sn4[k & 1], 0, 0, 0);
+        sn4[2 + (k & 1)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], qB[(k + 1) & 7], sn4[2 + (k & 1)], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      if constexpr (i + PD < 16) {
+        opnd[i + PD] = operand(Tag<i + PD>{}, slot);
+        __builtin_amdgcn_sched_group_barrier(0x100, ((i + PD) & 1) ? 2 : 1, 0);
+      } else if (stream) {
+        pre[i + PD - 16] = operand(Tag<i + PD - 16>{}, next);
+        __builtin_amdgcn_sched_group_barrier(0x100, ((i + PD) & 1) ? 2 : 1, 0);
+      }
+    });
+    for (int d = 0; d < 4; d++) for (int r = 0; r < 4; r++) sprev[4 * d + r] = sn4[d][r];
+  };
+#else
   auto burst = [&](int slot, int next, bool stream) {
     bf16x8 opnd[16];
     static_for<0, PD>([&](auto idx) { opnd[decltype(idx)::value] = pre[decltype(idx)::value]; });
@@ -74,9 +111,23 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
     });
     sprev = sn;
   };
+#endif
   auto softmax = [&]() {
     f32x16 s = sprev;
     asm volatile("" : "+v"(s));
+#ifdef LEAN
+    const float l_old = l_run;
+    unsigned pk[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      bf16x2 w;
+      w[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, nmc));
+      w[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, nmc));
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(w, ones, l_run, false);
+      pk[e] = __builtin_bit_cast(unsigned, w);
+    }
+    if (__builtin_amdgcn_ballot_w64(!(l_run <= 1.15e18f)) != 0) { m_run += 1.f; nmc = -m_run * c2; l_run = l_old * 0.5f; }
+#else
     const float mc = m_run * c2;
     float ps0 = 0.f, ps1 = 0.f; unsigned pk[8];
 #pragma unroll
@@ -90,8 +141,45 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
     const float ps = ps0 + ps1;
     if (__builtin_amdgcn_ballot_w64(!(ps <= 65536.f)) != 0) { m_run += 1.f; l_run *= 0.5f; }
     l_run += ps;
+#endif
     pb[0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
     pb[1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+  };
+  // one step with the softmax of the previous scores interleaved between the 16 MFMAs: NV vector
+  // instructions after every MFMA
+  auto fused = [&](int slot, int next, auto nv) {
+    constexpr int NV = decltype(nv)::value;   // 3: fma/exp + cvt|dot per packet; 4: two packets of softmax per MFMA pair ...
+    bf16x8 opnd[16];
+    static_for<0, PD>([&](auto idx) { opnd[decltype(idx)::value] = pre[decltype(idx)::value]; });
+    f32x16 sn; for (int r = 0; r < 16; r++) sn[r] = 0.f;
+    f32x16 s = sprev;
+    const float mc = m_run * c2;
+    float ps0 = 0.f, ps1 = 0.f; unsigned pk[8]; float ex[16];
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, 16>([&](auto idx) {
+      constexpr int i = decltype(idx)::value, k = i >> 1;
+      if constexpr (i & 1) o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], pb[k >> 2], o[k & 3], 0, 0, 0);
+      else sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], qB[k], sn, 0, 0, 0);
+      if constexpr (i + PD < 16) opnd[i + PD] = operand(Tag<i + PD>{}, slot);
+      else pre[i + PD - 16] = operand(Tag<i + PD - 16>{}, next);
+      ex[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -mc));
+      if constexpr (i & 1) {
+        bf16x2 w; w[0] = (__bf16)ex[i - 1]; w[1] = (__bf16)ex[i];
+        pk[k] = __builtin_bit_cast(unsigned, w);
+      } else if constexpr (i >= 2) {
+        const bf16x2 w = __builtin_bit_cast(bf16x2, pk[k - 1]);
+        if ((k - 1) & 1) ps1 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps1, false); else ps0 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps0, false);
+      }
+      if constexpr (NV == 3 || (i & 1)) __builtin_amdgcn_sched_barrier(0);
+    });
+    ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk[7]), ones, ps1, false);
+    const float ps = ps0 + ps1;
+    __builtin_amdgcn_sched_barrier(0);
+    if (__builtin_amdgcn_ballot_w64(!(ps <= 65536.f)) != 0) { m_run += 1.f; l_run *= 0.5f; }
+    l_run += ps;
+    pb[0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
+    pb[1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+    sprev = sn;
   };
   const long long t0 = clock64();
   if (role == MFMA) {
@@ -99,27 +187,57 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
     for (int it = 0; it < iters; it++) burst((it & 7) * 8192, ((it + 1) & 7) * 8192, true);
   } else if (role == SOFTMAX) {
     for (int it = 0; it < iters; it++) { softmax(); sprev[it & 15] += l_run * 1e-12f; }
+  } else if (role == FUSED) {
+    prefetch(0);
+    for (int it = 0; it < iters; it++) {
+      fused((it & 7) * 8192, ((it + 1) & 7) * 8192, Tag<NVT>{});
+      if (sync != 0) __builtin_amdgcn_s_barrier();
+    }
   } else if (role == ALTERNATE) {
     if (wave < 4) {                               // softmax first, MFMAs second
       for (int it = 0; it < iters; it++) {
         const int slot = (it & 7) * 8192;
         prefetch(slot);
         __builtin_amdgcn_sched_barrier(0);
+#if PRIO == 1
+        __builtin_amdgcn_s_setprio(3);
+#endif
         softmax();
         __builtin_amdgcn_sched_barrier(0);
+#if PRIO == 1
+        __builtin_amdgcn_s_setprio(0);
+#endif
         if (sync == 2) __builtin_amdgcn_s_barrier();
+#if PRIO == 2
+        __builtin_amdgcn_s_setprio(3);
+#endif
         burst(slot, 0, false);
+#if PRIO == 2
+        __builtin_amdgcn_s_setprio(0);
+#endif
         __builtin_amdgcn_sched_barrier(0);
         if (sync != 0) __builtin_amdgcn_s_barrier();
       }
     } else {                                      // MFMAs first, softmax second
       prefetch(0);
       for (int it = 0; it < iters; it++) {
+#if PRIO == 2
+        __builtin_amdgcn_s_setprio(3);
+#endif
         burst((it & 7) * 8192, 0, false);
         __builtin_amdgcn_sched_barrier(0);
+#if PRIO == 2
+        __builtin_amdgcn_s_setprio(0);
+#endif
         if (sync == 2) __builtin_amdgcn_s_barrier();
+#if PRIO == 1
+        __builtin_amdgcn_s_setprio(3);
+#endif
         softmax();
         __builtin_amdgcn_sched_barrier(0);
+#if PRIO == 1
+        __builtin_amdgcn_s_setprio(0);
+#endif
         prefetch(((it + 1) & 7) * 8192);
         __builtin_amdgcn_sched_barrier(0);
         if (sync != 0) __builtin_amdgcn_s_barrier();
@@ -128,21 +246,25 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
   }
   const long long t1 = clock64();
   float acc = l_run + m_run;
+#ifdef M16
+  for (int d = 0; d < 16; d++) for (int r = 0; r < 4; r++) acc += o16[d][r];
+#endif
   for (int d = 0; d < 4; d++) for (int r = 0; r < 16; r++) acc += o[d][r] + sprev[r];
   out[blockIdx.x * 512 + threadIdx.x] = acc;
   if (lane == 0) cyc[blockIdx.x * 8 + wave] = t1 - t0;
 }
 
-static void run(const char* name, int roleA, int roleB, int sync) {
+static void run(const char* name, int roleA, int roleB, int sync, int nvsel = 4) {
   const int nblk = 256, iters = 2000;
   float* out; long long* cyc;
   CK(hipMalloc(&out, nblk * 512 * 4)); CK(hipMalloc(&cyc, nblk * 8 * 8));
-  CK(hipFuncSetAttribute((const void*)k_mix, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+  auto kern = nvsel == 3 ? k_mix<3> : nvsel == 5 ? k_mix<5> : k_mix<4>;
+  CK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   float ms = 0;
   for (int rep = 0; rep < 3; rep++) {
     CK(hipEventRecord(e0));
-    hipLaunchKernelGGL(k_mix, dim3(nblk), dim3(512), 131072, 0, out, cyc, iters, roleA, roleB, sync);
+    hipLaunchKernelGGL(kern, dim3(nblk), dim3(512), 131072, 0, out, cyc, iters, roleA, roleB, sync, nvsel);
     CK(hipEventRecord(e1)); CK(hipDeviceSynchronize()); CK(hipEventElapsedTime(&ms, e0, e1));
   }
   long long h[8]; CK(hipMemcpy(h, cyc, 64, hipMemcpyDeviceToHost));
@@ -157,8 +279,11 @@ int main() {
   run("softmax + softmax", SOFTMAX, SOFTMAX, 0);
   run("MFMA on waves 0-3, softmax on waves 4-7", MFMA, SOFTMAX, 0);
   run("softmax on waves 0-3, MFMA on waves 4-7", SOFTMAX, MFMA, 0);
-  run("alternating as the kernel does, no barrier", ALTERNATE, ALTERNATE, 0);
-  run("alternating as the kernel does, one barrier per step", ALTERNATE, ALTERNATE, 1);
-  run("alternating as the kernel does, barrier per half step", ALTERNATE, ALTERNATE, 2);
+  run("alternating as the 8-wave kernel does, no barrier", ALTERNATE, ALTERNATE, 0);
+  run("alternating as the 8-wave kernel does, one barrier per step", ALTERNATE, ALTERNATE, 1);
+  run("alternating as the 8-wave kernel does, barrier per half step", ALTERNATE, ALTERNATE, 2);
+  run("fused: softmax between the MFMAs of the same wave, one wave per SIMD", FUSED, IDLE, 0, 3);
+  run("fused, both waves, no barrier", FUSED, FUSED, 0, 3);
+  run("fused, both waves, one barrier per step", FUSED, FUSED, 1, 3);
   return 0;
 }
