@@ -10,6 +10,7 @@
 //   -DPRIO=1 / -DPRIO=2   raise the wave priority (s_setprio 3) around the softmax / around the MFMA burst
 //   -DM16                 the burst uses 32 v_mfma_f32_16x16x32_bf16 instead of 16 of the 32x32x16 shape
 //   -DLEAN                the softmax adds its row sum straight into the running sum (one dependent chain)
+//   -DNOLDS               the MFMA operands come from registers instead of LDS (what the LDS reads cost)
 // The "fused" runs interleave the softmax instructions between the MFMAs of the same wave.
 #include <hip/hip_runtime.h>
 #ifndef PRIO
@@ -59,6 +60,9 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
   bf16x8 pre[PD];
   auto operand = [&](auto idx, int slot) -> bf16x8 {
     constexpr int i = decltype(idx)::value, k = i >> 1;
+#ifdef NOLDS
+    return qB[i & 7];                          // operands from registers: the burst reads no LDS
+#endif
     if constexpr (i & 1) return rdtr(va_addr[k & 3] + slot + 16 * (k >> 2) * 256);
     else return rd128(ka_addr[k] + slot);
   };
