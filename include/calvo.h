@@ -300,6 +300,18 @@ int calvo_pool_cancel(calvo_pool* pool, int64_t ticket);
  * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */
 int calvo_attn_kernel_ms(calvo_ctx* ctx, int layer, float* ms);
 
+/* Planning helper (host code, needs no GPU): what calvo_prefill_attn would launch for a bf16, head
+ * dim 128 batch with these lengths on a device with n_cus compute units.  prefix_blocks / suffix_lens:
+ * HOST arrays of n_reqs.  Outputs (any may be NULL): *kernel as in calvo_attn_kernel_info,
+ * *tile_tokens = suffix tokens per work item, *pieces = split-KV pieces a tile's context is cut into at
+ * most (1 = no cut; pieces are never shorter than 48 sub-tiles of 32 keys), *n_workgroups of the
+ * launch.  The choice replays the launch on the device's workgroup slots and cuts tiles when that
+ * shortens it: too few tiles for the chip (the paper's "long context, short query" requests), or a
+ * workgroup count just above a whole number of rounds.  CALVO_EINVAL for bad arguments. */
+int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
+                    const int32_t* suffix_lens, int32_t n_reqs, int32_t* kernel, int32_t* tile_tokens,
+                    int32_t* pieces, int32_t* n_workgroups);
+
 /* Measurement helper: which attention kernel the most recent calvo_prefill_attn for `layer` chose
  * (*kernel: 3 = 8-wave workgroups with 64-token tiles, 4 = two 4-wave workgroups per CU with 32-token
  * tiles, 0-2 = comparison variants, -1 = the vector-ALU kernel for fp32 pools / other head dims) and

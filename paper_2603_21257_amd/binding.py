@@ -22,7 +22,7 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
            "calvo_pool_cancel", "calvo_last_error"]
@@ -92,6 +92,8 @@ def lib() -> C.CDLL:
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
+        L.calvo_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.calvo_attn_kernel_info.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         dp = C.POINTER(C.c_double)
         L.calvo_cost_fit.argtypes = [dp, dp, C.c_int, dp, dp]
@@ -282,6 +284,20 @@ def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pip
 
 
 ATTN_KERNEL_NAMES = {3: "calvo::pipe::attn_pipe_kernel", 4: "calvo::duo::attn_duo_kernel", -1: "calvo::attn_simple_kernel"}
+
+
+def calvo_attn_plan(n_q_heads: int, n_kv_heads: int, n_cus: int, prefix_blocks, suffix_lens) -> dict:
+    """What calvo_prefill_attn would launch for these lengths: kernel id, tile size, pieces per tile, workgroups."""
+    pb = np.ascontiguousarray(prefix_blocks, dtype=np.int32)
+    sl = np.ascontiguousarray(suffix_lens, dtype=np.int32)
+    if pb.shape != sl.shape:
+        raise ValueError("prefix_blocks and suffix_lens need one entry per request")
+    out = [C.c_int32() for _ in range(4)]
+    rc = lib().calvo_attn_plan(n_q_heads, n_kv_heads, n_cus, pb.ctypes.data_as(C.POINTER(C.c_int32)),
+                               sl.ctypes.data_as(C.POINTER(C.c_int32)), len(pb), *[C.byref(o) for o in out])
+    if rc != CALVO_OK:
+        raise CalvoError(rc, "invalid planning argument")
+    return dict(zip(("kernel", "tile_tokens", "pieces", "workgroups"), (o.value for o in out)))
 
 
 def calvo_attn_kernel_info(ctx: int, layer: int):

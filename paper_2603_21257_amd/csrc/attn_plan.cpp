@@ -1,0 +1,103 @@
+// Planning of an attention launch on the host.  A tile of suffix tokens normally is one work item
+// that walks its whole context.  Short suffixes over long contexts (the paper's main regime,
+// Section 2.2 and Table 1) give too few tiles for the chip, and some batches give a workgroup
+// count just above a whole number of rounds; in both cases every tile's context is cut into pieces
+// that run as separate workgroups and are merged afterwards.  How many pieces is decided by
+// replaying the launch: workgroups start in grid order on the first free workgroup slot, a piece
+// costs its sub-tiles plus a fixed pipeline fill and drain, cut tiles pay the merge.
+#include "attn_plan.h"
+
+#include <algorithm>
+#include <functional>
+
+#include "../../include/calvo.h"
+
+namespace calvo {
+
+std::vector<PlanTile> plan_tiles(const int32_t* prefix_blocks, const int32_t* suffix_lens, int n_reqs, int tile_tokens) {
+  std::vector<PlanTile> tiles;
+  for (int r = 0; r < n_reqs; r++) {
+    const int nt = (suffix_lens[r] + tile_tokens - 1) / tile_tokens;
+    for (int t = 0; t < nt; t++) {
+      const int64_t keys = (int64_t)prefix_blocks[r] * 16 + std::min<int64_t>((int64_t)(t + 1) * tile_tokens, suffix_lens[r]);
+      tiles.push_back({r, t, (int32_t)((keys + 31) / 32)});
+    }
+  }
+  std::stable_sort(tiles.begin(), tiles.end(), [](const PlanTile& a, const PlanTile& b) { return a.n_sub > b.n_sub; });
+  return tiles;
+}
+
+// The kernels run a piece of n sub-tiles as one fill step, unrolled steady iterations and a few
+// slower drain steps; lengths of the form 8k + 2 leave two drain steps in either kernel.
+int plan_piece_len(int n_sub, int want, const PlanParams& p) {
+  const int n = std::max(1, std::min(want, p.force_splits ? n_sub : n_sub / p.split_min));
+  int len = (n_sub + n - 1) / n;
+  if (n > 1 && !p.force_splits) len = (len + 5) / 8 * 8 + 2;
+  return len;
+}
+
+int plan_pieces(const std::vector<PlanTile>& tiles, const PlanParams& p) {
+  if (p.force_splits) return p.force_splits;
+  const int64_t wgs = (int64_t)tiles.size() * p.n_head_groups;
+  if (wgs <= 0 || wgs > 16 * (int64_t)p.wg_slots) return 1;     // many rounds: the last one hardly matters
+  const int cands[] = {1, 2, 3, 4, 5, 6, 8, 12, 16, 24, 32, 48, 64};
+  int want = 1;
+  double best = 0;
+  std::vector<int64_t> heap;
+  for (int n : cands) {
+    if (n > 1 && wgs * n > 16 * (int64_t)p.wg_slots) break;
+    heap.assign((size_t)p.wg_slots, 0);            // min-heap of the times at which workgroup slots become free
+    auto cmp = std::greater<int64_t>();
+    bool cut = false;
+    int64_t end = 0;
+    for (const PlanTile& t : tiles) {
+      const int len = plan_piece_len(t.n_sub, n, p);
+      const int np = (t.n_sub + len - 1) / len;
+      cut |= np > 1;
+      for (int k = 0; k < np; k++) {
+        const int64_t cost = std::min(t.n_sub, (k + 1) * len) - k * len + p.split_fill;
+        for (int h = 0; h < p.n_head_groups; h++) {
+          std::pop_heap(heap.begin(), heap.end(), cmp);
+          heap.back() += cost;
+          end = std::max(end, heap.back());
+          std::push_heap(heap.begin(), heap.end(), cmp);
+        }
+      }
+    }
+    const double span = (double)end + (cut ? p.split_fill : 0);
+    if (n == 1 || span < best * 0.98) {            // a cut has to win by 2 % over what is chosen so far
+      best = span;
+      want = n;
+    }
+    if (!cut && n > 1) break;                       // longer cuts are refused by split_min: nothing changes
+  }
+  return want;
+}
+
+}  // namespace calvo
+
+extern "C" int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
+                               const int32_t* suffix_lens, int32_t n_reqs, int32_t* kernel, int32_t* tile_tokens,
+                               int32_t* pieces, int32_t* n_workgroups) {
+  using namespace calvo;
+  if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || n_cus <= 0 || n_reqs < 0) return CALVO_EINVAL;
+  if (n_reqs > 0 && (!prefix_blocks || !suffix_lens)) return CALVO_EINVAL;
+  for (int r = 0; r < n_reqs; r++)
+    if (prefix_blocks[r] < 0 || suffix_lens[r] < 0) return CALVO_EINVAL;
+  const int hw = attn_heads_per_wg(n_q_heads, n_kv_heads);
+  const int variant = attn_mfma_choose(suffix_lens, n_reqs, hw);
+  const int tt = attn_mfma_tile_tokens(variant, hw);
+  const std::vector<PlanTile> tiles = plan_tiles(prefix_blocks, suffix_lens, n_reqs, tt);
+  PlanParams p{n_q_heads / hw, n_cus * (8 / attn_mfma_waves_per_wg(variant)), 48, 30, 0};
+  const int want = attn_mfma_splits_context(variant) ? plan_pieces(tiles, p) : 1;
+  int64_t items = 0;
+  for (const PlanTile& t : tiles) {
+    const int len = plan_piece_len(t.n_sub, want, p);
+    items += (t.n_sub + len - 1) / len;
+  }
+  if (kernel) *kernel = variant;
+  if (tile_tokens) *tile_tokens = tt;
+  if (pieces) *pieces = want;
+  if (n_workgroups) *n_workgroups = (int32_t)(items * p.n_head_groups);
+  return CALVO_OK;
+}

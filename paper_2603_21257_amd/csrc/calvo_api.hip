@@ -868,7 +868,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const calvo_config& cf = c->cfg;
   const int G = cf.n_q_heads / cf.n_kv_heads;
   const bool mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
-  const int HW = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+  const int HW = attn_heads_per_wg(cf.n_q_heads, cf.n_kv_heads);
   int variant = 0;
   if (mfma) {
     std::vector<int32_t> slens(n_reqs);
@@ -895,12 +895,9 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     blob.push_back(cu_suffix[r]);
     n_tab += (size_t)nt + kTablePad + (nt & 1);
   }
-  // Work items.  A tile of suffix tokens normally is one item that walks its whole context.  When
-  // the batch has too few tiles to give every CU a workgroup (short suffixes over long contexts),
-  // every tile's context is cut into pieces of at least split_min sub-tiles that run as separate
-  // workgroups and are merged afterwards; the number of pieces aims at one workgroup per CU
-  // (measured best: more, shorter pieces pay the pipeline fill and drain more often).  Tiles are ordered heaviest first; the pieces of a tile are consecutive.
-  struct Tile { int32_t req, tile, n_sub; };
+  // Work items: tiles of suffix tokens, heaviest first, each possibly cut into split-KV pieces
+  // (consecutive work items) that the merge kernel combines; see attn_plan.cpp.
+  typedef PlanTile Tile;
   std::vector<Tile> tiles;
   std::vector<WorkItem> items;
   std::vector<int32_t> split_tiles;
@@ -913,77 +910,24 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   const bool chunked = mfma && cb > 0 && attn_mfma_splits_context(variant) && !c->force_splits;
   if (mfma) {
-    for (int r = 0; r < n_reqs; r++) {
-      const int nt = (reqs[r].suffix_len + tile_tokens - 1) / tile_tokens;
-      for (int t = 0; t < nt; t++) {
-        const int64_t keys = (int64_t)reqs[r].n_prefix_blocks * kBlockTokens +
-                             std::min<int64_t>((int64_t)(t + 1) * tile_tokens, reqs[r].suffix_len);
-        tiles.push_back({r, t, (int32_t)((keys + 31) / 32)});
-      }
-    }
-    std::stable_sort(tiles.begin(), tiles.end(), [](const Tile& a, const Tile& b) { return a.n_sub > b.n_sub; });
-    const int NHG = cf.n_q_heads / HW;
-    const int64_t wgs = (int64_t)tiles.size() * NHG;
-    // pieces a tile of n_sub sub-tiles is cut into when `want` are asked for
-    // length of the pieces a tile of n_sub sub-tiles is cut into when `want` pieces are asked for.
-    // The kernel runs a piece of n sub-tiles as one fill step, 8-step steady iterations and
-    // n - 8k >= 2 slower drain steps, so lengths of the form 8k + 2 waste the least.
-    auto piece_len = [&](int n_sub, int want) {
-      const int n = std::max(1, std::min(want, c->force_splits ? n_sub : n_sub / c->split_min));
-      int len = (n_sub + n - 1) / n;
-      if (n > 1 && !c->force_splits) len = (len + 5) / 8 * 8 + 2;
-      return len;
-    };
-    const int64_t wg_slots = (int64_t)c->n_cus * (8 / attn_mfma_waves_per_wg(variant));   // workgroups resident at a time
+    std::vector<int32_t> pblocks(n_reqs), slens(n_reqs);
+    for (int r = 0; r < n_reqs; r++) { pblocks[r] = reqs[r].n_prefix_blocks; slens[r] = reqs[r].suffix_len; }
+    tiles = plan_tiles(pblocks.data(), slens.data(), n_reqs, tile_tokens);
+    const PlanParams pp{cf.n_q_heads / HW, c->n_cus * (8 / attn_mfma_waves_per_wg(variant)), c->split_min, c->split_fill,
+                        c->force_splits};
+    auto piece_len = [&](int n_sub, int want) { return plan_piece_len(n_sub, want, pp); };
     int want = 1;
     if (attn_mfma_splits_context(variant) && !chunked) {
-      if (c->force_splits) want = c->force_splits;
-      else if (wgs > 0 && wgs <= 16 * wg_slots) {
-        // Choose the number of pieces by replaying the launch: workgroups start in grid order on
-        // the first free workgroup slot (one or two per CU), a piece costs its sub-tiles plus a fixed
-        // pipeline fill and drain, cut tiles pay the merge.  This covers both too few workgroups
-        // for the chip and a workgroup count just above a whole number of rounds (640 equal
-        // workgroups on 256 CUs take three rounds; cut in two they take five half-length rounds).
-        // The decision depends only on the batch's lengths and is kept for the following layers.
-        std::vector<int64_t> key;
-        key.reserve(2 * n_reqs);
-        key.push_back(variant);
-        for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
-        if (key == c->plan_key) want = c->plan_want;
-        else {
-          const int cands[] = {1, 2, 3, 4, 5, 6, 8, 12, 16, 24, 32, 48, 64};
-          double best = 0;
-          std::vector<int64_t> heap;
-          for (int n : cands) {
-            if (n > 1 && wgs * n > 16 * wg_slots) break;
-            heap.assign((size_t)wg_slots, 0);            // min-heap of the times at which workgroup slots become free
-            auto cmp = std::greater<int64_t>();
-            bool cut = false;
-            int64_t end = 0;
-            for (const Tile& t : tiles) {
-              const int len = piece_len(t.n_sub, n);
-              const int np = (t.n_sub + len - 1) / len;
-              cut |= np > 1;
-              for (int k = 0; k < np; k++) {
-                const int64_t cost = std::min(t.n_sub, (k + 1) * len) - k * len + c->split_fill;
-                for (int h = 0; h < NHG; h++) {
-                  std::pop_heap(heap.begin(), heap.end(), cmp);
-                  heap.back() += cost;
-                  end = std::max(end, heap.back());
-                  std::push_heap(heap.begin(), heap.end(), cmp);
-                }
-              }
-            }
-            const double span = (double)end + (cut ? c->split_fill : 0);
-            if (n == 1 || span < best * 0.98) {          // a cut has to win by 2 % over what is chosen so far
-              best = span;
-              want = n;
-            }
-            if (!cut && n > 1) break;                     // longer cuts are refused by split_min: nothing changes
-          }
-          c->plan_key = key;
-          c->plan_want = want;
-        }
+      // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
+      // is kept for the following layers
+      std::vector<int64_t> key;
+      key.reserve(2 * n_reqs + 1);
+      key.push_back(variant);
+      for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
+      if (!c->force_splits && key == c->plan_key) want = c->plan_want;
+      else {
+        want = plan_pieces(tiles, pp);
+        if (!c->force_splits) { c->plan_key = key; c->plan_want = want; }
       }
     }
     if (chunked) {

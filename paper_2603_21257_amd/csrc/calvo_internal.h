@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_plan.h"
+
 namespace calvo {
 
 // One request as the attention kernels see it (int32 x 4, device memory).
@@ -67,15 +69,10 @@ hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_
                                  int32_t blk_bytes, int grid, hipStream_t stream);
 hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
-// which MFMA kernel serves a batch with these suffix lengths (see attn_mfma.hip); the other calls take its answer
-int attn_mfma_choose(const int32_t* suffix_lens, int n_reqs, int heads_per_wg);
 hipError_t launch_attn_mfma(int variant, const AttnParams& p, hipStream_t stream);
-int attn_mfma_tile_tokens(int variant, int heads_per_wg);
-bool attn_mfma_splits_context(int variant);   // whether that kernel handles work items with n_splits > 1
 hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
 hipError_t launch_attn_duo(const AttnParams& p, hipStream_t stream);
 int attn_duo_tile_tokens(int heads_per_wg);
-int attn_mfma_waves_per_wg(int variant);
 // combines the pieces of every split tile into out (bf16); n_split_tiles entries in split_tiles =
 // indices of the first work item of each split tile
 hipError_t launch_merge_splits(const AttnParams& p, const int32_t* split_tiles, int n_split_tiles, hipStream_t stream);
