@@ -22,25 +22,13 @@
 // for V) of K(t+4) and V(t+2), reads K(t+1) and V(t-1), and ends with s_waitcnt vmcnt(8) + one
 // barrier: everything requested two or more steps earlier has landed, i.e. K up to t+2 and V up
 // to t.  The slots written at step t (those of K(t) and V(t-2)) were last read in step t-1.
-#include "calvo_internal.h"
+#include "attn_common.h"
 
 namespace calvo {
 namespace duo {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
+using namespace attn;
 
-constexpr int kD = 128;
-constexpr int kSK = 32;                        // keys per sub-tile / ring slot
-constexpr int kRow = 256;                      // bytes per token row of one head
-constexpr int kSlot = kSK * kRow;              // 8192
 constexpr int kRing = 4;
 constexpr int kVBase = kRing * kSlot;          // V ring follows the K ring
 // furthest sub-tile whose block offsets are fetched: n_pipe + 3 * kRing, with n_pipe at most
@@ -49,62 +37,6 @@ constexpr int kVBase = kRing * kSlot;          // V ring follows the K ring
 static_assert(kTablePad >= 8 * kRing, "block table padding too small for the ring depth");
 constexpr float kLazyBound = 65536.f;   // a lane's partial row sum of 16 weights may reach 2^16 before the reference is raised
 constexpr int kLdsBytes = 2 * kRing * kSlot;   // 65536: two 4-wave workgroups per CU
-
-template <int V>
-struct Tag { static constexpr int value = V; };
-// f(Tag<B>{}), f(Tag<B+1>{}), ... f(Tag<E-1>{}): a loop whose index is a compile-time constant
-template <int B, int E, typename F>
-__device__ inline void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(Tag<B>{});
-    static_for<B + 1, E>(f);
-  }
-}
-constexpr int kPD = 4;   // LDS operand reads run this many MFMAs ahead
-
-// lanes [32,64) of a <-> lanes [0,32) of b (the compiler builtin for this instruction returns
-// its first result twice, hence inline asm)
-__device__ inline void half_swap(float& a, float& b) {
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-}
-__device__ inline float half_swap_max(float v) {
-  float a = v, b = v;
-  half_swap(a, b);
-  return fmaxf(a, b);
-}
-__device__ inline float half_swap_sum(float v) {
-  float a = v, b = v;
-  half_swap(a, b);
-  return a + b;
-}
-
-// 64 lanes x 16 bytes from global memory (uniform base + per-lane byte offset) to 1 KiB of LDS
-// starting at lds_addr (uniform).  Completion is tracked by vmcnt.  No "memory" clobber on
-// purpose: every read of the deposited data sits behind wait_vm + a workgroup barrier, and a
-// clobber would stop the compiler from keeping the block-table loads on the scalar unit.
-__device__ inline void dma_1k(const unsigned char* sbase, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(voff), "s"(sbase), "s"(lds_addr));
-}
-// compiler-level fence for one value: it is 'rewritten' here, so its producers stay above this
-// point and its consumers below it; emits no instruction
-template <typename T>
-__device__ inline void pin(T& x) {
-  asm volatile("" : "+v"(x));
-}
-template <int N>
-__device__ inline void wait_vm() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
-}
-
-__device__ inline bf16x8 read_k(const lds_u8* a) { return *(const __attribute__((address_space(3))) bf16x8*)a; }
-__device__ inline bf16x8 read_vt(const lds_u8* a) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a + 8 * kRow));
-  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, both);
-}
 
 // 240 of the 256 registers a wave may have at two waves per SIMD (the attribute counts half of
 // the unified VGPR+AGPR file on this target): the remaining 32 per SIMD lane
