@@ -53,7 +53,7 @@ def _release_arena():
     release_cached_memory()
 
 
-def run_full(cfg, pool_layers, attn_layers, rows_per_req, n_layers=None):
+def run_full(cfg, pool_layers, attn_layers, rows_per_req, n_layers=None, tail_chunks=0, tail_layers=6):
     w = wl.make_config(cfg, with_payload=False, n_layers=n_layers)
     s = w.shape
     L, T, B = s.n_layers, w.total_suffix, s.block_tokens
@@ -74,7 +74,11 @@ def run_full(cfg, pool_layers, attn_layers, rows_per_req, n_layers=None):
                           staging_bytes=staging)
     try:
         reqs = hh.make_requests(w, host)
-        cb.calvo_kv_ingest(ctx, reqs, 0, L)
+        if tail_chunks:                                  # bench.py's configuration for load-bound workloads
+            per = -(-max(r.n_prefix_blocks for r in w.requests) // tail_chunks)
+            cb.calvo_kv_ingest_chunked(ctx, reqs, 0, L, [0] * (L - tail_layers) + [per + (per & 1)] * tail_layers)
+        else:
+            cb.calvo_kv_ingest(ctx, reqs, 0, L)
         for l in range(L):
             cb.calvo_prefill_attn(ctx, l, q[l], ks[l], vs[l], out[l], reqs, w.cu_suffix, 0.0)
     finally:
@@ -127,8 +131,9 @@ def test_workload2_full_size():
 
 
 def test_workload3_full_size_64k_context():
-    """The benchmark workload: prefix 61440, suffix 4096, 32 layers."""
-    run_full(3, pool_layers=range(32), attn_layers=[0, 15, 31], rows_per_req=40)
+    """The benchmark workload: prefix 61440, suffix 4096, 32 layers, as bench.py times it: the last 6 layers
+    loaded in 4 chunks and attended chunk by chunk (layers 26 and 31 of the checked ones), the others whole."""
+    run_full(3, pool_layers=range(32), attn_layers=[0, 15, 26, 31], rows_per_req=40, tail_chunks=4)
 
 
 def test_workload4_full_size_varlen_batch_shared_prefix():

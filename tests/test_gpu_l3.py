@@ -165,7 +165,7 @@ def test_chunk_signals_follow_the_loader():
         assert not cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_QUERY)        # 48 ms away
         assert cb.calvo_chunk_event(ctx, 0, 1, cb.CALVO_EV_HOST_WAIT)
         t1 = time.perf_counter() - t0
-        assert 0.014 < t1 < 0.040, t1                                        # two chunks of 8 ms each on the link
+        assert 0.014 < t1 < 0.045, t1                                        # two chunks of 8 ms each on the link
         assert not cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_QUERY)
         assert not cb.calvo_layer_event(ctx, 0, cb.CALVO_EV_QUERY)
         assert cb.calvo_chunk_event(ctx, 0, 5, cb.CALVO_EV_HOST_WAIT)
