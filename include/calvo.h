@@ -247,9 +247,12 @@ int calvo_sched_pick(int policy, const calvo_cost_model* model, const calvo_job*
 
 /* Replays a whole trace on one server.  load_s / comp_s: the time each job's loading and computation
  * actually take (HOST arrays of n; NULL = the model's estimates).  pipelined == 0: one job at a time,
- * load then compute.  pipelined != 0: loading and computation are separate stages (Section 3.1), a
+ * load then compute.  pipelined == 1: loading and computation are separate stages (Section 3.1), a
  * job is taken when the loading stage is free and computes when its load has finished and the compute
- * stage is free.  Whenever the (loading) stage is free and a job has arrived, the policy picks; if
+ * stage is free, in loading order.  pipelined == 2: both stages serve their highest-priority ready
+ * request ("the highest-priority request" of Section 3.1, per stage): the loading stage picks among
+ * the arrived jobs, the compute stage among the loaded ones, decisions in time order, the compute stage
+ * first at equal times.  Whenever the (loading) stage is free and a job has arrived, the policy picks; if
  * none has arrived the server idles until the next arrival.  Outputs: start_s[i] (loading starts) and
  * finish_s[i] (first token; TTFT_i = finish_s[i] - arrival_s). */
 int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_job* jobs, int n, const double* load_s,

@@ -80,8 +80,54 @@ def pick(policy, model, jobs, done, now):
     return -1 if best is None else best[2]
 
 
+def simulate_staged(policy, model, jobs, load_s=None, comp_s=None):
+    """Replay with loading and computation as two stages that each serve their highest-priority ready
+    request (Section 3.1: a stage's dispatcher works on "the highest-priority request" whose lower-level
+    blocks are ready): the loading stage picks among the requests that have arrived, the compute
+    stage among those whose loading has finished.  Both are non-preemptive.  Decisions are taken in
+    time order; when both stages could decide at the same instant, the compute stage goes first."""
+    n = len(jobs)
+    t_load = [load_s[i] if load_s is not None else estimate(model, jobs[i])[0] for i in range(n)]
+    t_comp = [comp_s[i] if comp_s is not None else estimate(model, jobs[i])[1] for i in range(n)]
+    start, finish = [0.0] * n, [0.0] * n
+    load_end = [math.inf] * n
+    taken = [False] * n           # by the loading stage
+    done = [False] * n            # by the compute stage
+    loader_free = compute_free = -math.inf
+    for _ in range(2 * n):
+        t_l = math.inf
+        if not all(taken):
+            t_l = max(loader_free, min(jobs[i][0] for i in range(n) if not taken[i]))
+        t_c = math.inf
+        ready = [load_end[i] for i in range(n) if taken[i] and not done[i]]
+        if ready:
+            t_c = max(compute_free, min(ready))
+        if t_c <= t_l:
+            best = None
+            for i in range(n):
+                if taken[i] and not done[i] and load_end[i] <= t_c:
+                    key = (priority(policy, model, jobs[i]), jobs[i][0], i)
+                    if best is None or key < best:
+                        best = key
+            i = best[2]
+            finish[i] = t_c + t_comp[i]
+            compute_free = finish[i]
+            done[i] = True
+        else:
+            i = pick(policy, model, jobs, taken, t_l)
+            start[i] = t_l
+            load_end[i] = t_l + t_load[i]
+            loader_free = load_end[i]
+            taken[i] = True
+    return start, finish
+
+
 def simulate(policy, model, jobs, load_s=None, comp_s=None, pipelined=False):
-    """Replay of the trace on one server; returns (start, finish) lists."""
+    """Replay of the trace on one server; returns (start, finish) lists.  pipelined: False/0 = one
+    request at a time; True/1 = loading overlaps the previous request's computation, computation in
+    loading order; 2 = simulate_staged."""
+    if int(pipelined) == 2:
+        return simulate_staged(policy, model, jobs, load_s, comp_s)
     n = len(jobs)
     done = [False] * n
     start, finish = [0.0] * n, [0.0] * n

@@ -270,8 +270,8 @@ def calvo_sched_pick(policy: int, model, jobs, done, now: float) -> int:
     return out.value
 
 
-def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pipelined: bool = False):
-    """Returns (start_s, finish_s) as numpy arrays."""
+def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pipelined=False):
+    """Returns (start_s, finish_s) as numpy arrays.  pipelined: 0 / False, 1 / True, or 2 (see the header)."""
     m = calvo_cost_model(*model) if model is not None else None
     n = len(jobs)
     start, sp = _darr(np.zeros(max(n, 1)))
@@ -279,7 +279,7 @@ def calvo_sched_simulate(policy: int, model, jobs, load_s=None, comp_s=None, pip
     la = _darr(load_s) if load_s is not None else (None, None)
     ca = _darr(comp_s) if comp_s is not None else (None, None)
     _sched_check(lib().calvo_sched_simulate(policy, C.byref(m) if m is not None else None, _job_array(jobs), n, la[1], ca[1],
-                                            1 if pipelined else 0, sp, fp))
+                                            int(pipelined), sp, fp))
     return start[:n], fin[:n]
 
 

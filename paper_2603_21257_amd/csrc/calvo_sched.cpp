@@ -105,6 +105,43 @@ int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_
   std::vector<unsigned char> done((size_t)n, 0);
   double loader_free = -std::numeric_limits<double>::infinity();
   double compute_free = -std::numeric_limits<double>::infinity();
+  if (pipelined == 2) {
+    // Two stages that each serve their highest-priority ready request (Section 3.1): the loading
+    // stage picks among the requests that have arrived, the compute stage among those whose loading
+    // has finished; decisions in time order, the compute stage first at equal times.
+    const double inf = std::numeric_limits<double>::infinity();
+    std::vector<unsigned char> taken((size_t)n, 0);
+    std::vector<double> load_end((size_t)n, inf);
+    for (int step = 0; step < 2 * n; step++) {
+      double t_l = inf, t_c = inf, first_arrival = inf, first_ready = inf;
+      for (int i = 0; i < n; i++) {
+        if (!taken[i] && jobs[i].arrival_s < first_arrival) first_arrival = jobs[i].arrival_s;
+        if (taken[i] && !done[i] && load_end[i] < first_ready) first_ready = load_end[i];
+      }
+      if (first_arrival < inf) t_l = loader_free > first_arrival ? loader_free : first_arrival;
+      if (first_ready < inf) t_c = compute_free > first_ready ? compute_free : first_ready;
+      if (t_c <= t_l) {
+        int best = -1;
+        Key bk{};
+        for (int i = 0; i < n; i++) {
+          if (!taken[i] || done[i] || !(load_end[i] <= t_c)) continue;
+          Key k{0.0, jobs[i].arrival_s, i};
+          priority_of(policy, model, jobs[i], &k.priority);
+          if (best < 0 || k < bk) { best = i; bk = k; }
+        }
+        finish_s[best] = t_c + (comp_s ? comp_s[best] : model_comp(*model, jobs[best]));
+        compute_free = finish_s[best];
+        done[best] = 1;
+      } else {
+        const int i = pick(policy, model, jobs, taken.data(), n, t_l);
+        start_s[i] = t_l;
+        load_end[i] = t_l + (load_s ? load_s[i] : model_load(*model, jobs[i]));
+        loader_free = load_end[i];
+        taken[i] = 1;
+      }
+    }
+    return CALVO_OK;
+  }
   for (int served = 0; served < n; served++) {
     // the server (its loading stage, when pipelined) takes the next job when it is free and a job
     // has arrived; otherwise it idles until the next arrival

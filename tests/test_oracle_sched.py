@@ -142,6 +142,73 @@ def test_replay_is_work_conserving_and_never_starts_before_arrival(policy, pipel
         assert max(fin) <= max(fin_serial) + 1e-12
 
 
+def test_staged_replay_by_hand():
+    """Both stages serve their highest-priority ready request (Section 3.1).  Worked by hand, times given
+    directly: A (load 1, compute 10) and B (load 1, compute 5) arrive at 0, D (load 1, compute 1) at 1.5,
+    SJF.  Loading: B at 0 (6 < 11), A at 1, D at 2.  Compute: B 1-6; at 6 both A (loaded at 2) and D
+    (loaded at 3) wait and D is the shorter job: D 6-7, A 7-17.  In loading order (the plain pipelined
+    replay) A would compute 6-16 and D 16-17."""
+    model = (1.0, 0.0, 1.0, 0.0)                       # cost = tokens, so priorities are the times themselves
+    jobs = [(0.0, math.inf, 1, 10), (0.0, math.inf, 1, 5), (1.5, math.inf, 1, 1)]
+    start, fin = so.simulate(so.SJF, model, jobs, pipelined=2)
+    assert start == [1.0, 0.0, 2.0] and fin == [17.0, 6.0, 7.0]
+    start, fin = so.simulate(so.SJF, model, jobs, pipelined=True)
+    assert start == [1.0, 0.0, 2.0] and fin == [16.0, 6.0, 17.0]
+    # FIFO keeps arrival order in both stages: A loads first and B, D wait behind its computation
+    start, fin = so.simulate(so.FIFO, model, jobs, pipelined=2)
+    assert start == [0.0, 1.0, 2.0] and fin == [11.0, 16.0, 17.0]
+
+
+@pytest.mark.parametrize("policy", [so.FIFO, so.SJF, so.SJF_PT, so.LSTF, so.EDF])
+def test_staged_replay_conserves_work_and_respects_both_stages(policy):
+    rng = np.random.default_rng(70 + policy)
+    n = 14
+    jobs = random_jobs(rng, n, all_at_zero=False)
+    load = [float(x) for x in rng.uniform(0.01, 0.3, n)]
+    comp = [float(x) for x in rng.uniform(0.005, 0.4, n)]
+    start, fin = so.simulate(policy, MODEL, jobs, load, comp, 2)
+    for i in range(n):
+        assert start[i] >= jobs[i][0] and fin[i] >= start[i] + load[i] + comp[i] - 1e-12
+    by_load = sorted(range(n), key=lambda i: start[i])
+    for a, b in zip(by_load, by_load[1:]):                      # the loading stage holds one job at a time
+        assert start[b] >= start[a] + load[a] - 1e-12
+    by_comp = sorted(range(n), key=lambda i: fin[i])
+    for a, b in zip(by_comp, by_comp[1:]):                      # and so does the compute stage
+        assert fin[b] - comp[b] >= fin[a] - 1e-12
+    # the compute stage never idles while a loaded job waits: every compute start is either the end of the
+    # previous computation or the moment the job's own loading finished
+    for k, i in enumerate(by_comp):
+        cs = fin[i] - comp[i]
+        prev_end = fin[by_comp[k - 1]] if k else -math.inf
+        assert abs(cs - prev_end) < 1e-9 or abs(cs - (start[i] + load[i])) < 1e-9 or \
+            any(abs(cs - (start[j] + load[j])) < 1e-9 for j in range(n))
+    # with nothing to load and everybody present, the staged replay is the single-server one
+    zero = [0.0] * n
+    present = [(0.0, j[1], j[2], j[3]) for j in jobs]
+    assert so.simulate(policy, MODEL, present, zero, comp, 2)[1] == so.simulate(policy, MODEL, present, zero, comp, False)[1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_staged_sjf_beats_loading_order_on_average_when_compute_queues(seed):
+    """Brute force over all compute orders of a small loaded backlog: when every job is loaded before the
+    compute stage frees up, the staged SJF replay computes them in the order that minimises the mean."""
+    rng = np.random.default_rng(300 + seed)
+    n = 6
+    comp = [float(x) for x in rng.uniform(0.1, 2.0, n)]
+    load = [1e-3] * n                                           # everything is loaded by t = 6 ms
+    model = (0.0, 0.0, 1.0, 0.0)
+    jobs = [(0.0, math.inf, 1, int(c * 1000)) for c in comp]    # SJF priority = compute tokens
+    blocker = [(0.0, math.inf, 1, 1)]                           # a first job that occupies the compute stage
+    all_jobs = blocker + jobs
+    times_l = [1e-3] + load
+    times_c = [1.0] + comp
+    _, fin = so.simulate(so.SJF, model, all_jobs, times_l, times_c, 2)
+    best = min(sum(itertools.accumulate(comp[i] for i in perm)) for perm in itertools.permutations(range(n)))
+    # the blocker (fewest tokens) loads and computes first, ending at 1.001; the rest follow back to back
+    got = sum(f - fin[0] for f in fin[1:])
+    assert abs(got - best) < 1e-9
+
+
 def test_line_fit_closed_forms():
     a, b = so.fit_line([1000, 3000], [0.1, 0.5])
     assert abs(a - 2e-4) < 1e-15 and abs(b + 0.1) < 1e-12

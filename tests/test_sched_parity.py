@@ -27,7 +27,7 @@ def trace(seed, n):
 
 @pytest.mark.parametrize("seed", range(4))
 @pytest.mark.parametrize("cpol,opol", POLICIES)
-@pytest.mark.parametrize("pipelined", [False, True])
+@pytest.mark.parametrize("pipelined", [False, True, 2])
 def test_replay_matches_oracle_exactly(seed, cpol, opol, pipelined):
     jobs = trace(seed, 40)
     rng = np.random.default_rng(1000 + seed)
