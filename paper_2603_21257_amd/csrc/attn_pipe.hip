@@ -205,8 +205,12 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   // ---- pipeline registers: S and P of two consecutive sub-tiles
   f32x16 sbuf[2];
   bf16x8 pbuf[2][2];
+  // Rescale of O that a raised reference asks for: al[b] per lane, needed[b] for the wave (a
+  // scalar: the steady path sets it with one scalar move and spends no vector instruction on it).
   float al[2] = {1.f, 1.f};
   bool chg[2] = {false, false};
+  bool needed[2] = {false, false};
+  float nmc_run = INFINITY;     // -m_run * c2, kept beside m_run (m_run = -inf before the first sub-tile)
 
   auto rescale = [&](float a) {
 #pragma unroll
@@ -236,6 +240,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     changed = (m_new != m_run);
     m_run = m_new;
     mc = m_new * c2;
+    nmc_run = -mc;
   };
   // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the rounded
   // values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
@@ -321,21 +326,20 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     // results of each half to its side of the barrier: the compiler may not move them across.
     auto valu_half = [&]() {
       pin(m_run);
+      pin(nmc_run);
       const f32x16& s = sbuf[C];
-      float a_acc = 1.f;
-      bool changed = false;
+      bool raised = false;
       float ps;
       unsigned pk[8];
       // weights of accumulator registers 2e, 2e+1, rounded to bf16 once; the row sum adds the
       // rounded values (v_dot2 against (1,1)) so numerator and denominator use the same numbers
       auto weights = [&]() {
-        const float mc = m_run * c2;
         float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           bf16x2 w;
-          w[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, -mc));
-          w[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, -mc));
+          w[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e], c2, nmc_run));
+          w[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * e + 1], c2, nmc_run));
           if (e & 1) ps1 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps1, false);
           else ps0 = __builtin_amdgcn_fdot2_f32_bf16(w, ones, ps0, false);
           pk[e] = __builtin_bit_cast(unsigned, w);
@@ -354,17 +358,18 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
 #pragma unroll
         for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
         const float m_new = fmaxf(m_run, half_swap_max(mx));
-        a_acc = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-        changed = (m_new != m_run);
+        const float a_acc = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+        raised = __builtin_amdgcn_ballot_w64(m_new != m_run) != 0;
         m_run = m_new;
+        nmc_run = -m_new * c2;
         l_run *= a_acc;
+        al[C] = a_acc;
         weights();
       }
       l_run += ps;
       pbuf[C][0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
       pbuf[C][1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
-      al[C] = a_acc;
-      chg[C] = changed;
+      needed[C] = raised;
       pin(pbuf[C][0]);
       pin(pbuf[C][1]);
       pin(l_run);
@@ -378,7 +383,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
       pin(qB[0]);
       pin(pbuf[N][0]);
       pin(pbuf[N][1]);
-      if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
+      if (needed[N]) rescale(al[N]);
       f32x16 sn;
 #pragma unroll
       for (int r = 0; r < 16; r++) sn[r] = 0.f;
@@ -431,10 +436,13 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
     request_v(t + 5);
     if (t + 1 < n_pipe) qk((t + 1) & 7, sbuf[N]);
     if (t >= 1 && t <= n_pipe) {
-      if (__builtin_amdgcn_ballot_w64(chg[N]) != 0) rescale(al[N]);
+      if (needed[N]) rescale(al[N]);
       pv((t - 1) & 7, pbuf[N]);
     }
-    if (t < n_pipe) sm_all(sbuf[C], pbuf[C], al[C], chg[C]);
+    if (t < n_pipe) {
+      sm_all(sbuf[C], pbuf[C], al[C], chg[C]);
+      needed[C] = __builtin_amdgcn_ballot_w64(chg[C]) != 0;
+    }
     wait_vm<8>();      // as in a steady step: K up to t+3 and V up to t+1 have landed
     __syncthreads();
   };
