@@ -25,7 +25,7 @@ def check(w, **kw):
 
 
 def test_config1_fp32_full():
-    """BASELINE config 1 in full: fp32, 8Q/2KV heads, D=64, P=1024, S=128, pool of 256 slots."""
+    """Workload 1 in full: fp32, 8Q/2KV heads, D=64, P=1024, S=128, pool of 256 slots."""
     w = wl.make_config(1)
     mx, mean = check(w)
     print(f"cfg1 fp32 max {mx:.2e} mean {mean:.2e}")
