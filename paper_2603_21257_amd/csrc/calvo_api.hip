@@ -299,7 +299,7 @@ struct L3Request {            // what the loader keeps of a calvo_request after 
   const unsigned char* src;   // pageable "remote" memory
   int64_t layer_stride;
   int64_t first, nblk;
-  size_t tab_off;
+  int64_t tab_off;            // index of its block 0 in the device table (entries exist from `first` on)
 };
 
 struct L3Job {
@@ -525,7 +525,7 @@ namespace {
 // Front part shared by both ingest calls: validation, source pointers, block tables to the device.
 // pinned: the sources must be page-locked (and device-mapped for the zero-copy mode).
 int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end, bool pinned,
-                   std::vector<const unsigned char*>& src, std::vector<size_t>& tab_off) {
+                   std::vector<const unsigned char*>& src, std::vector<int64_t>& tab_off) {
   if (layer_begin < 0 || layer_end > c->cfg.n_layers || layer_begin > layer_end)
     return fail(CALVO_EINVAL, "layer range [%d, %d) outside [0, %d]", layer_begin, layer_end, c->cfg.n_layers);
   std::vector<char> seen;
@@ -533,10 +533,13 @@ int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int laye
   if (rc != CALVO_OK) return rc;
   src.assign(n_reqs, nullptr);
   tab_off.assign(n_reqs, 0);
+  // The device table holds the slots of the blocks that are loaded, request after request, so that
+  // requests whose host blocks follow each other also have consecutive table entries (one transfer
+  // and one scatter can then serve several of them).  tab_off[r] + j is the entry of block j >= first.
   size_t n_tab = 0;
   for (int r = 0; r < n_reqs; r++) {
-    tab_off[r] = n_tab;
-    n_tab += (size_t)reqs[r].n_prefix_blocks;
+    tab_off[r] = (int64_t)n_tab - reqs[r].first_ingest_block;
+    n_tab += (size_t)(reqs[r].n_prefix_blocks - reqs[r].first_ingest_block);
     if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) continue;
     void* dp = const_cast<void*>(reqs[r].host_kv);
     if (pinned) {
@@ -565,8 +568,9 @@ int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int laye
     if (rc != CALVO_OK) return rc;
     if (c->tab_ing_pending) { HIP_TRY(hipEventSynchronize(c->ev_tab_ing)); c->tab_ing_pending = false; }
     for (int r = 0; r < n_reqs; r++)
-      if (reqs[r].n_prefix_blocks)
-        memcpy(c->h_tab_ing + tab_off[r], reqs[r].block_table, (size_t)reqs[r].n_prefix_blocks * 4);
+      if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block)
+        memcpy(c->h_tab_ing + tab_off[r] + reqs[r].first_ingest_block, reqs[r].block_table + reqs[r].first_ingest_block,
+               (size_t)(reqs[r].n_prefix_blocks - reqs[r].first_ingest_block) * 4);
     HIP_TRY(hipMemcpyAsync(c->d_tab_ing, c->h_tab_ing, n_tab * 4, hipMemcpyHostToDevice, c->s_scatter));
     HIP_TRY(hipEventRecord(c->ev_tab_ing, c->s_scatter));
     c->tab_ing_pending = true;
@@ -589,7 +593,7 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
   int rc = join_loader(c);
   if (rc != CALVO_OK) return rc;
   std::vector<const unsigned char*> src;
-  std::vector<size_t> tab_off;
+  std::vector<int64_t> tab_off;
   rc = prepare_ingest(c, reqs, n_reqs, layer_begin, layer_end, true, src, tab_off);
   if (rc != CALVO_OK) return rc;
   if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
@@ -626,11 +630,24 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
       }
     }
     if (cb == 0) {
-      for (int r = 0; r < n_reqs; r++)
-        if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block) {
-          rc = load_range(l, r, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks);
-          if (rc != CALVO_OK) return rc;
+      // requests whose host blocks (and hence table entries) follow each other load as one run:
+      // every transfer boundary costs PCIe time
+      for (int r = 0; r < n_reqs;) {
+        if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) { r++; continue; }
+        int64_t j1 = reqs[r].n_prefix_blocks;
+        int r2 = r + 1;
+        for (; r2 < n_reqs; r2++) {
+          const calvo_request& a = reqs[r], &b = reqs[r2];
+          if (b.n_prefix_blocks == b.first_ingest_block) continue;
+          const unsigned char* end = src[r] + (int64_t)l * a.host_layer_stride + j1 * (int64_t)c->blk_bytes;
+          const unsigned char* beg = src[r2] + (int64_t)l * b.host_layer_stride + b.first_ingest_block * (int64_t)c->blk_bytes;
+          if (end != beg || tab_off[r] + j1 != tab_off[r2] + b.first_ingest_block) break;
+          j1 += b.n_prefix_blocks - b.first_ingest_block;     // continue request r's block numbering through b
         }
+        rc = load_range(l, r, reqs[r].first_ingest_block, j1);
+        if (rc != CALVO_OK) return rc;
+        r = r2;
+      }
     } else {
       // chunk k = block indices [k cb, (k+1) cb) of every request (a shared run sits at the same
       // indices in every table, so once chunk k is in, all blocks below (k+1) cb are resident)
@@ -721,7 +738,7 @@ int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
   int rc = join_loader(c);
   if (rc != CALVO_OK) return rc;
   std::vector<const unsigned char*> src;
-  std::vector<size_t> tab_off;
+  std::vector<int64_t> tab_off;
   rc = prepare_ingest(c, reqs, n_reqs, layer_begin, layer_end, false, src, tab_off);
   if (rc != CALVO_OK) return rc;
   {
