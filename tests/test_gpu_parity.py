@@ -134,6 +134,28 @@ def test_staged_copy_engine_ingest_is_bit_exact(staging_blocks, n_staging, n_cop
     check(w, staging_bytes=staging_blocks * shape.blk_bytes, n_staging=n_staging, n_copy_streams=n_copy)
 
 
+@pytest.mark.parametrize("order", ["as laid out", "reversed", "interleaved"])
+@pytest.mark.parametrize("staging_blocks", [0, 7, 64])
+def test_batch_ingest_in_any_request_order(order, staging_blocks):
+    """Requests whose host blocks follow each other are loaded as one run per layer (one transfer, one
+    scatter); given in another order, or with a request in between that has nothing to load, they are
+    separate runs.  The pool must hold the same bytes either way."""
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 160)
+    w = wl.make_custom(shape, [(10 * 16, 10), (0, 20), (20 * 16, 5), (6 * 16, 7), (33 * 16, 0)], seed=3100, shared_blocks=0)
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(shape), shape, dev)
+    host = hh.to_torch(w.host_kv, shape, pin=True)
+    ctx = cb.calvo_create(3, 8, 2, 128, cb.CALVO_BF16, 160, pool, staging_bytes=staging_blocks * shape.blk_bytes)
+    try:
+        reqs = hh.make_requests(w, host)
+        idx = {"as laid out": [0, 1, 2, 3, 4], "reversed": [4, 3, 2, 1, 0], "interleaved": [2, 0, 4, 1, 3]}[order]
+        cb.calvo_kv_ingest(ctx, [reqs[i] for i in idx], 0, 3)
+        assert cb.calvo_layer_event(ctx, 2, cb.CALVO_EV_HOST_WAIT)
+    finally:
+        cb.calvo_destroy(ctx)
+    hh.assert_pool_bit_exact(hh.to_numpy_stored(pool, shape), hh.sentinel_pool_after_ingest(w))
+
+
 def test_no_suffix_and_no_prefix_edge_cases():
     shape = wl.Shape(1, 8, 2, 128, "bf16", 64)
     w = wl.make_custom(shape, [(128, 0)], seed=3)           # nothing to compute: ingest only
