@@ -138,14 +138,19 @@ def main():
     # later layers, and starting it on landed chunks moves compute-stream work forward
     plan = {"chunk_blocks": None}
 
-    def set_tail_chunks(n):
-        if n <= 0 or L < 1:
+    def set_tail_chunks(n, head=False):
+        """n chunks per layer for the last --tail-layers layers, or (head) for the first layer only."""
+        longest = max(r.n_prefix_blocks for r in w.requests)
+        if n <= 0 or L < 1 or longest < 2:
             plan["chunk_blocks"] = None
             return
-        longest = max(r.n_prefix_blocks for r in w.requests)
         per = max(2, -(-longest // n))
-        nt = max(1, min(L, args.tail_layers))
-        plan["chunk_blocks"] = [0] * (L - nt) + [per + (per & 1)] * nt
+        per += per & 1
+        if head:
+            plan["chunk_blocks"] = [per] + [0] * (L - 1)
+        else:
+            nt = max(1, min(L, args.tail_layers))
+            plan["chunk_blocks"] = [0] * (L - nt) + [per] * nt
 
     host_trace = []
 
@@ -193,10 +198,15 @@ def main():
         ingest_only()
         t_ing = min(timed(ingest_only) for _ in range(2))
         t_att = min(timed(attn_only) for _ in range(2))
+        head_chunks = False
         if args.tail_chunks < 0:
-            # pays when loading bounds the step and a layer's attention is a sizeable part of a layer's load
+            # The last layers in chunks pay when loading bounds the step and a layer's attention is a sizeable
+            # part of a layer's load.  When attention bounds the step, the first layer in chunks lets it start
+            # after a quarter of that layer's load (single requests: a batch would trade its one transfer per
+            # layer for one per request and chunk).
             args.tail_chunks = 4 if t_ing > t_att >= 0.5 * t_ing else 0
-        set_tail_chunks(args.tail_chunks)
+            head_chunks = t_att > t_ing and L > 1 and len(w.requests) == 1
+        set_tail_chunks(4 if head_chunks else args.tail_chunks, head=head_chunks)
         # the interpreter's cyclic collector would otherwise run a full pass (tens of milliseconds with torch
         # loaded) in the middle of some step's enqueue loop
         import gc
@@ -240,7 +250,8 @@ def main():
                        "prefix_tokens": [r.prefix_len for r in w.requests],
                        "suffix_tokens": [r.suffix_len for r in w.requests],
                        "ingest": "zero-copy kernel" if args.staging_mib == 0 else f"copy engine, {args.staging_mib} MiB staging x{args.n_staging or 2}",
-                       "chunked_tail": f"{args.tail_layers} layers x {args.tail_chunks} chunks" if args.tail_chunks else "none"},
+                       "chunked_layers": ("first layer x 4 chunks" if head_chunks else
+                                          f"last {args.tail_layers} layers x {args.tail_chunks} chunks" if args.tail_chunks else "none")},
             "ttft_ms": {"mean": round(ms, 3), "median": round(statistics.median(step_ms), 3),
                         "min": round(min(step_ms), 3), "each": [round(x, 3) for x in step_ms], "lower_bound": round(ttft_lb, 3),
                         "frac_of_lower_bound": round(ttft_lb / ms, 4)},
