@@ -237,6 +237,25 @@ int ensure_att_blob(calvo_ctx* c, size_t n) {
 }
 
 
+// Room for the split-KV partial results of `slots` (work item, head group, wave) triples.  Growing
+// frees the old buffers, hence waits for the compute stream; contexts for bf16 / head-dim-128
+// pools start with room for the short-query batches (kPartialSlots0), so only long chunk-granular
+// layers ever grow it.
+constexpr size_t kPartialSlots0 = 4096;      // 68 MB
+int ensure_partials(calvo_ctx* c, size_t slots) {
+  if (slots <= c->part_slots) return CALVO_OK;
+  if (c->part_slots) HIP_TRY(hipStreamSynchronize(c->s_compute));
+  if (c->part_o) (void)hipFree(c->part_o);
+  if (c->part_ml) (void)hipFree(c->part_ml);
+  c->part_o = c->part_ml = nullptr;
+  c->part_slots = 0;
+  slots = std::max(slots, kPartialSlots0);
+  HIP_TRY(hipMalloc((void**)&c->part_o, slots * 32 * 128 * sizeof(float)));
+  HIP_TRY(hipMalloc((void**)&c->part_ml, slots * 32 * 2 * sizeof(float)));
+  c->part_slots = slots;
+  return CALVO_OK;
+}
+
 // Waits for a running L3 loader and returns its status (CALVO_OK if none ran).
 int join_loader(calvo_ctx* c) {
   if (c->loader_started) {
@@ -501,6 +520,10 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   CREATE_TRY(hipEventCreateWithFlags(&c->ev_tab_ing, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&c->ev_att, hipEventDisableTiming));
 #undef CREATE_TRY
+  if (cfg->dtype == CALVO_BF16 && cfg->head_dim == 128) {
+    const int prc = ensure_partials(c, kPartialSlots0);
+    if (prc != CALVO_OK) { destroy_partial(c); return prc; }
+  }
   *out = c;
   return CALVO_OK;
 }
@@ -1020,17 +1043,8 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   rc = ensure_att_blob(c, blob.size());
   if (rc != CALVO_OK) return rc;
   if (!split_tiles.empty()) {
-    const size_t slots = items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant);
-    if (slots > c->part_slots) {
-      HIP_TRY(hipStreamSynchronize(c->s_compute));
-      if (c->part_o) (void)hipFree(c->part_o);
-      if (c->part_ml) (void)hipFree(c->part_ml);
-      c->part_o = c->part_ml = nullptr;
-      c->part_slots = 0;
-      HIP_TRY(hipMalloc((void**)&c->part_o, slots * 32 * 128 * sizeof(float)));
-      HIP_TRY(hipMalloc((void**)&c->part_ml, slots * 32 * 2 * sizeof(float)));
-      c->part_slots = slots;
-    }
+    rc = ensure_partials(c, items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant));
+    if (rc != CALVO_OK) return rc;
   }
   const bool same = c->att_len == blob.size() && memcmp(c->h_att, blob.data(), blob.size() * 4) == 0;
   if (!same) {
