@@ -1049,9 +1049,10 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const bool same = c->att_len == blob.size() && memcmp(c->h_att, blob.data(), blob.size() * 4) == 0;
   if (!same) {
     if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
+    c->att_len = 0;                       // the device copy is unknown until the transfer is queued
     memcpy(c->h_att, blob.data(), blob.size() * 4);
-    c->att_len = blob.size();
     HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att, blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+    c->att_len = blob.size();
     HIP_TRY(hipEventRecord(c->ev_att, c->s_compute));
     c->att_pending = true;
   }

@@ -11,6 +11,8 @@
 //   -DM16                 the burst uses 32 v_mfma_f32_16x16x32_bf16 instead of 16 of the 32x32x16 shape
 //   -DLEAN                the softmax adds its row sum straight into the running sum (one dependent chain)
 //   -DNOLDS               the MFMA operands come from registers instead of LDS (what the LDS reads cost)
+//   -DW12                 twelve waves per workgroup (three per SIMD, at most 168 registers each); waves 4-11 take the second role
+//   -DACCO                the O accumulators of the burst live in accumulation registers (a[..]) instead of v[..]
 // The "fused" runs interleave the softmax instructions between the MFMAs of the same wave.
 #include <hip/hip_runtime.h>
 #ifndef PRIO
@@ -37,13 +39,18 @@ __device__ inline bf16x8 rdtr(const lds_u8* a) {
 constexpr int PD = 4;
 enum Role { IDLE = 0, MFMA = 1, SOFTMAX = 2, ALTERNATE = 3, FUSED = 4 };
 // sync (ALTERNATE only): 0 no barrier, 1 one barrier per step, 2 one per half step
+#ifdef W12
+constexpr int kThreads = 768;    // twelve waves: three per SIMD; waves 4-11 take role B
+#else
+constexpr int kThreads = 512;
+#endif
 template <int NVT>
-__global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int iters, int roleA, int roleB, int sync, int nvsel) {
+__global__ void __launch_bounds__(kThreads, kThreads == 512 ? 2 : 1) k_mix(float* out, long long* cyc, int iters, int roleA, int roleB, int sync, int nvsel) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const lds_u8* lds = (const lds_u8*)smem;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int role = wave < 4 ? roleA : roleB;
-  for (int i = threadIdx.x; i < 131072 / 4; i += 512) ((unsigned*)smem)[i] = 0x3c003c00u + i % 7;
+  for (int i = threadIdx.x; i < 131072 / 4; i += kThreads) ((unsigned*)smem)[i] = 0x3c003c00u + i % 7;
   __syncthreads();
   bf16x8 qB[8], pb[2];
   for (int k = 0; k < 8; k++) for (int j = 0; j < 8; j++) qB[k][j] = (__bf16)(0.01f * (k + j + lane % 3));
@@ -102,6 +109,13 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
     f32x16 sn; for (int r = 0; r < 16; r++) sn[r] = 0.f;
     static_for<0, 16>([&](auto idx) {
       constexpr int i = decltype(idx)::value, k = i >> 1;
+#ifdef ACCO
+      // accumulators named by register file: O in accumulation registers, S in ordinary ones
+      if constexpr (i & 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o[k & 3]) : "v"(opnd[i]), "v"(pb[k >> 2]));
+      else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(sn) : "v"(opnd[i]), "v"(qB[k]));
+      if constexpr (i + PD < 16) opnd[i + PD] = operand(Tag<i + PD>{}, slot);
+      else if (stream) pre[i + PD - 16] = operand(Tag<i + PD - 16>{}, next);
+#else
       if constexpr (i & 1) o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], pb[k >> 2], o[k & 3], 0, 0, 0);
       else sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], qB[k], sn, 0, 0, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -112,6 +126,7 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
         pre[i + PD - 16] = operand(Tag<i + PD - 16>{}, next);
         __builtin_amdgcn_sched_group_barrier(0x100, ((i + PD) & 1) ? 2 : 1, 0);
       }
+#endif
     });
     sprev = sn;
   };
@@ -254,25 +269,27 @@ __global__ void __launch_bounds__(512, 2) k_mix(float* out, long long* cyc, int 
   for (int d = 0; d < 16; d++) for (int r = 0; r < 4; r++) acc += o16[d][r];
 #endif
   for (int d = 0; d < 4; d++) for (int r = 0; r < 16; r++) acc += o[d][r] + sprev[r];
-  out[blockIdx.x * 512 + threadIdx.x] = acc;
-  if (lane == 0) cyc[blockIdx.x * 8 + wave] = t1 - t0;
+  out[blockIdx.x * kThreads + threadIdx.x] = acc;
+  if (lane == 0) cyc[blockIdx.x * 16 + wave] = t1 - t0;
 }
 
 static void run(const char* name, int roleA, int roleB, int sync, int nvsel = 4) {
   const int nblk = 256, iters = 2000;
   float* out; long long* cyc;
-  CK(hipMalloc(&out, nblk * 512 * 4)); CK(hipMalloc(&cyc, nblk * 8 * 8));
+  CK(hipMalloc(&out, nblk * kThreads * 4)); CK(hipMalloc(&cyc, nblk * 16 * 8));
   auto kern = nvsel == 3 ? k_mix<3> : nvsel == 5 ? k_mix<5> : k_mix<4>;
   CK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   float ms = 0;
   for (int rep = 0; rep < 3; rep++) {
     CK(hipEventRecord(e0));
-    hipLaunchKernelGGL(kern, dim3(nblk), dim3(512), 131072, 0, out, cyc, iters, roleA, roleB, sync, nvsel);
+    hipLaunchKernelGGL(kern, dim3(nblk), dim3(kThreads), 131072, 0, out, cyc, iters, roleA, roleB, sync, nvsel);
     CK(hipEventRecord(e1)); CK(hipDeviceSynchronize()); CK(hipEventElapsedTime(&ms, e0, e1));
   }
-  long long h[8]; CK(hipMemcpy(h, cyc, 64, hipMemcpyDeviceToHost));
-  printf("%-58s waves 0-3 %5.0f ticks/iter, waves 4-7 %5.0f ticks/iter, kernel %.3f ms\n", name, (double)h[0] / iters, (double)h[4] / iters, ms);
+  long long h[16]; CK(hipMemcpy(h, cyc, 128, hipMemcpyDeviceToHost));
+  printf("%-58s waves 0-3 %5.0f ticks/iter, waves 4-7 %5.0f ticks/iter, kernel %.3f ms", name, (double)h[0] / iters, (double)h[4] / iters, ms);
+  if (kThreads == 768) printf(", waves 8-11 %5.0f ticks/iter", (double)h[8] / iters);
+  printf("\n");
   CK(hipFree(out)); CK(hipFree(cyc));
 }
 
