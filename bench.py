@@ -339,6 +339,9 @@ def cpu_baseline(w, host, q, ks, vs, out, n_rows):
     layers = sorted({0, L // 2, L - 1})
     rng = np.random.default_rng(w.seed + 99)
     per_req = max(4, n_rows // len(w.requests))
+    # keep the sample near 10-20 s of oracle time whatever the shape: about 3.5e9 (row, key, head) triples
+    ctx_sum = sum(r.prefix_len + r.suffix_len / 2 for r in w.requests if r.suffix_len)
+    per_req = max(8, min(per_req, int(3.5e9 / (len(layers) * s.n_q_heads * max(ctx_sum, 1)))))
     pairs = 0
     worst_max, means = 0.0, []
     t0 = time.perf_counter()
