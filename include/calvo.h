@@ -30,6 +30,18 @@
  *    k_suffix, v_suffix  [total suffix tokens][Hkv][D]
  * The paper names blocks, tiers and the context/query split but no block size,
  * layout or precision; these are this library's definitions.
+ *
+ * Threads: one thread at a time per context (the library's own loader thread
+ * aside); different contexts are independent.
+ *
+ * Environment (for tests and tuning; results stay within the stated tolerance
+ * whatever they are set to).  Read by calvo_create: CALVO_ATTN_SPLITS = n
+ * cuts every attention tile's context into n pieces; CALVO_SPLIT_MIN,
+ * CALVO_SPLIT_FILL = parameters of the automatic cut (shortest piece, cost of
+ * a workgroup's start and end, both in 32-key steps); CALVO_SCATTER_GRID =
+ * workgroups of the zero-copy scatter.  Read by every calvo_prefill_attn:
+ * CALVO_ATTN_VARIANT = 3 or 4 forces the 8-wave or the 4-wave bf16 kernel
+ * (other values 0-2: the unpipelined comparison kernels).
  */
 #ifndef CALVO_H
 #define CALVO_H
@@ -314,6 +326,21 @@ int calvo_attn_kernel_ms(calvo_ctx* ctx, int layer, float* ms);
 int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
                     const int32_t* suffix_lens, int32_t n_reqs, int32_t* kernel, int32_t* tile_tokens,
                     int32_t* pieces, int32_t* n_workgroups);
+
+/* Planning helper (host code, needs no GPU): the work items of that launch, in launch order.  A work
+ * item is one tile of tile_tokens suffix tokens of one request over a range of its context, counted
+ * in sub-tiles of 32 keys; the pieces of a cut tile follow each other and partition [0, ceil(keys the
+ * tile's last row sees / 32)).  chunk_blocks = 0: a layer loaded as a whole (pieces as calvo_attn_plan
+ * says); chunk_blocks > 0 (even): a layer loaded with calvo_kv_ingest_chunked in chunks of that many
+ * blocks - piece k of a tile then covers the sub-tiles of chunk k inside the request's prefix and
+ * belongs to launch k, which waits for chunk k only; the rest of the tile is its last piece, in the
+ * last launch, which waits for the whole layer.  items: HOST array of 6 * capacity int32, filled
+ * with (request, tile, first sub-tile, end sub-tile, pieces of the tile, launch) per work item;
+ * *n_items: their number.  CALVO_ENOMEM if capacity is too small (*n_items is set; items may be NULL
+ * with capacity 0 to ask for the count), CALVO_EINVAL for bad arguments. */
+int calvo_attn_plan_items(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
+                          const int32_t* suffix_lens, int32_t n_reqs, int32_t chunk_blocks, int32_t* items,
+                          int32_t capacity, int32_t* n_items);
 
 /* Measurement helper: which attention kernel the most recent calvo_prefill_attn for `layer` chose
  * (*kernel: 3 = 8-wave workgroups with 64-token tiles, 4 = two 4-wave workgroups per CU with 32-token

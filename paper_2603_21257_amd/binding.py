@@ -22,7 +22,7 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
            "calvo_pool_cancel", "calvo_last_error"]
@@ -94,6 +94,8 @@ def lib() -> C.CDLL:
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
         L.calvo_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.calvo_attn_plan_items.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                            C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
         L.calvo_attn_kernel_info.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         dp = C.POINTER(C.c_double)
         L.calvo_cost_fit.argtypes = [dp, dp, C.c_int, dp, dp]
@@ -298,6 +300,28 @@ def calvo_attn_plan(n_q_heads: int, n_kv_heads: int, n_cus: int, prefix_blocks, 
     if rc != CALVO_OK:
         raise CalvoError(rc, "invalid planning argument")
     return dict(zip(("kernel", "tile_tokens", "pieces", "workgroups"), (o.value for o in out)))
+
+
+def calvo_attn_plan_items(n_q_heads: int, n_kv_heads: int, n_cus: int, prefix_blocks, suffix_lens,
+                          chunk_blocks: int = 0) -> np.ndarray:
+    """The work items of that launch, in launch order: int32 array [n][6] of (request, tile, first sub-tile,
+    end sub-tile, pieces of the tile, launch index); chunk_blocks > 0: the layer was loaded in such chunks."""
+    pb = np.ascontiguousarray(prefix_blocks, dtype=np.int32)
+    sl = np.ascontiguousarray(suffix_lens, dtype=np.int32)
+    if pb.shape != sl.shape:
+        raise ValueError("prefix_blocks and suffix_lens need one entry per request")
+    i32p = C.POINTER(C.c_int32)
+    n = C.c_int32()
+    args = (n_q_heads, n_kv_heads, n_cus, pb.ctypes.data_as(i32p), sl.ctypes.data_as(i32p), len(pb), chunk_blocks)
+    rc = lib().calvo_attn_plan_items(*args, None, 0, C.byref(n))
+    if rc not in (CALVO_OK, CALVO_ENOMEM):
+        raise CalvoError(rc, "invalid planning argument")
+    out = np.zeros((n.value, 6), np.int32)
+    if n.value:
+        rc = lib().calvo_attn_plan_items(*args, out.ctypes.data_as(i32p), n.value, C.byref(n))
+        if rc != CALVO_OK:
+            raise CalvoError(rc, "invalid planning argument")
+    return out
 
 
 def calvo_attn_kernel_info(ctx: int, layer: int):

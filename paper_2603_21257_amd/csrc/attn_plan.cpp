@@ -74,7 +74,77 @@ int plan_pieces(const std::vector<PlanTile>& tiles, const PlanParams& p) {
   return want;
 }
 
+PlanItems plan_items(const std::vector<PlanTile>& tiles, int want, const PlanParams& p) {
+  PlanItems out;
+  for (const PlanTile& t : tiles) {
+    const int len = plan_piece_len(t.n_sub, want, p);
+    const int n = (t.n_sub + len - 1) / len;
+    const int32_t first = (int32_t)out.items.size();
+    if (n > 1) out.split_tiles.push_back(first);
+    for (int k = 0; k < n; k++) out.items.push_back({t.req, t.tile, k * len, std::min(t.n_sub, (k + 1) * len), n, first, 0, 0});
+  }
+  return out;
+}
+
+PlanItems plan_items_chunked(const std::vector<PlanTile>& tiles, const int32_t* prefix_blocks, int chunk_blocks, int n_chunks) {
+  PlanItems out;
+  out.groups.assign((size_t)n_chunks + 1, {});
+  const int sub_per_chunk = chunk_blocks / 2;
+  for (const PlanTile& t : tiles) {
+    const int full = prefix_blocks[t.req] / 2;                   // sub-tiles wholly inside the prefix
+    const int32_t first = (int32_t)out.items.size();
+    const int n = (full + sub_per_chunk - 1) / sub_per_chunk;    // pieces that follow the chunks
+    const int cut_end = std::min(full, n * sub_per_chunk);
+    const int total = n + (cut_end < t.n_sub ? 1 : 0);
+    if (total > 1) out.split_tiles.push_back(first);
+    for (int k = 0; k < n; k++) {
+      out.groups[(size_t)std::min(k, n_chunks)].push_back((int32_t)out.items.size());
+      out.items.push_back({t.req, t.tile, k * sub_per_chunk, std::min(full, (k + 1) * sub_per_chunk), total, first, 0, 0});
+    }
+    if (cut_end < t.n_sub) {
+      out.groups[(size_t)n_chunks].push_back((int32_t)out.items.size());
+      out.items.push_back({t.req, t.tile, cut_end, t.n_sub, total, first, 0, 0});
+    }
+  }
+  return out;
+}
+
 }  // namespace calvo
+
+extern "C" int calvo_attn_plan_items(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
+                                     const int32_t* suffix_lens, int32_t n_reqs, int32_t chunk_blocks, int32_t* items,
+                                     int32_t capacity, int32_t* n_items) {
+  using namespace calvo;
+  if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0 || n_cus <= 0 || n_reqs < 0) return CALVO_EINVAL;
+  if (n_reqs > 0 && (!prefix_blocks || !suffix_lens)) return CALVO_EINVAL;
+  if (chunk_blocks < 0 || (chunk_blocks & 1) || capacity < 0 || (capacity > 0 && !items) || !n_items) return CALVO_EINVAL;
+  int max_blocks = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    if (prefix_blocks[r] < 0 || suffix_lens[r] < 0) return CALVO_EINVAL;
+    max_blocks = std::max(max_blocks, prefix_blocks[r]);
+  }
+  const int hw = attn_heads_per_wg(n_q_heads, n_kv_heads);
+  const int variant = attn_mfma_choose(suffix_lens, n_reqs, hw);
+  const std::vector<PlanTile> tiles = plan_tiles(prefix_blocks, suffix_lens, n_reqs, attn_mfma_tile_tokens(variant, hw));
+  const PlanParams p{n_q_heads / hw, n_cus * (8 / attn_mfma_waves_per_wg(variant)), 48, 30, 0};
+  PlanItems pi;
+  if (chunk_blocks > 0 && attn_mfma_splits_context(variant)) {
+    pi = plan_items_chunked(tiles, prefix_blocks, chunk_blocks, (max_blocks + chunk_blocks - 1) / chunk_blocks);
+  } else {
+    pi = plan_items(tiles, attn_mfma_splits_context(variant) ? plan_pieces(tiles, p) : 1, p);
+  }
+  *n_items = (int32_t)pi.items.size();
+  if ((int64_t)pi.items.size() > capacity) return CALVO_ENOMEM;
+  std::vector<int32_t> launch(pi.items.size(), 0);
+  for (size_t g = 0; g < pi.groups.size(); g++)
+    for (int32_t i : pi.groups[g]) launch[(size_t)i] = (int32_t)g;
+  for (size_t i = 0; i < pi.items.size(); i++) {
+    const WorkItem& w = pi.items[i];
+    int32_t* o = items + 6 * i;
+    o[0] = w.req; o[1] = w.q_tile; o[2] = w.sub_begin; o[3] = w.sub_end; o[4] = w.n_splits; o[5] = launch[i];
+  }
+  return CALVO_OK;
+}
 
 extern "C" int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
                                const int32_t* suffix_lens, int32_t n_reqs, int32_t* kernel, int32_t* tile_tokens,

@@ -31,6 +31,28 @@ struct PlanParams {
   int force_splits;   // > 0: cut every tile into this many pieces (test knob)
 };
 
+// A work item is one workgroup's share of the attention of one request: a tile of suffix tokens
+// (tile_tokens of them) over the sub-tile range [sub_begin, sub_end) of its context (32-key
+// sub-tiles).  Normally a tile is one work item covering its whole context; a tile may be cut into
+// n_splits > 1 pieces (split-KV), which then run as separate workgroups, write partial results
+// (unnormalised O, running maximum, row sum) and are combined by a merge kernel; the pieces of one
+// tile are consecutive work items.  The device reads this struct as it is.
+struct WorkItem {
+  int32_t req;
+  int32_t q_tile;     // tile index inside the request's suffix
+  int32_t sub_begin;  // first 32-key sub-tile of this piece
+  int32_t sub_end;    // one past its last sub-tile (the last piece ends at the tile's causal limit)
+  int32_t n_splits;   // pieces the tile is cut into; 1 = the kernel writes the final output itself
+  int32_t first_item; // index of the tile's first piece
+  int32_t pad0, pad1;
+};
+
+struct PlanItems {
+  std::vector<WorkItem> items;
+  std::vector<int32_t> split_tiles;              // first work item of every cut tile
+  std::vector<std::vector<int32_t>> groups;      // chunk-granular layers: work item indices per launch; else empty
+};
+
 // the batch's tiles of tile_tokens suffix tokens, heaviest first
 std::vector<PlanTile> plan_tiles(const int32_t* prefix_blocks, const int32_t* suffix_lens, int n_reqs, int tile_tokens);
 
@@ -39,5 +61,15 @@ int plan_piece_len(int n_sub, int want, const PlanParams& p);
 
 // pieces per tile to ask for (1 = no cut), from a replay of the launch
 int plan_pieces(const std::vector<PlanTile>& tiles, const PlanParams& p);
+
+// work items of a whole-layer launch: every tile cut into pieces of plan_piece_len(n_sub, want)
+PlanItems plan_items(const std::vector<PlanTile>& tiles, int want, const PlanParams& p);
+
+// Work items of a layer that was loaded in n_chunks chunks of chunk_blocks block indices (even): piece
+// k of a tile covers the sub-tiles of chunk k that lie wholly inside the request's prefix and goes
+// into launch k, which needs blocks below (k + 1) * chunk_blocks only; what is left of the tile (the
+// end of the prefix that shares a sub-tile with the suffix, the suffix itself) is its last piece, in
+// launch n_chunks, which needs the whole layer.
+PlanItems plan_items_chunked(const std::vector<PlanTile>& tiles, const int32_t* prefix_blocks, int chunk_blocks, int n_chunks);
 
 }  // namespace calvo

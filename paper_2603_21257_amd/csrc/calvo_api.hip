@@ -937,74 +937,44 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   // Work items: tiles of suffix tokens, heaviest first, each possibly cut into split-KV pieces
   // (consecutive work items) that the merge kernel combines; see attn_plan.cpp.
-  typedef PlanTile Tile;
-  std::vector<Tile> tiles;
-  std::vector<WorkItem> items;
-  std::vector<int32_t> split_tiles;
-  std::vector<std::vector<int32_t>> groups;     // chunk-granular launches: work item indices per launch
+  PlanItems plan;
   int cb = 0, nck = 0;
   {
     std::lock_guard<std::mutex> lk(c->mu);
     cb = c->chunk_blocks[layer];
     nck = c->n_chunks[layer];
   }
+  // a layer loaded in chunks: attention follows the chunks, one launch behind each chunk's event
   const bool chunked = mfma && cb > 0 && attn_mfma_splits_context(variant) && !c->force_splits;
   if (mfma) {
     std::vector<int32_t> pblocks(n_reqs), slens(n_reqs);
     for (int r = 0; r < n_reqs; r++) { pblocks[r] = reqs[r].n_prefix_blocks; slens[r] = reqs[r].suffix_len; }
-    tiles = plan_tiles(pblocks.data(), slens.data(), n_reqs, tile_tokens);
+    const std::vector<PlanTile> tiles = plan_tiles(pblocks.data(), slens.data(), n_reqs, tile_tokens);
     const PlanParams pp{cf.n_q_heads / HW, c->n_cus * (8 / attn_mfma_waves_per_wg(variant)), c->split_min, c->split_fill,
                         c->force_splits};
-    auto piece_len = [&](int n_sub, int want) { return plan_piece_len(n_sub, want, pp); };
-    int want = 1;
-    if (attn_mfma_splits_context(variant) && !chunked) {
-      // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
-      // is kept for the following layers
-      std::vector<int64_t> key;
-      key.reserve(2 * n_reqs + 1);
-      key.push_back(variant);
-      for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
-      if (!c->force_splits && key == c->plan_key) want = c->plan_want;
-      else {
-        want = plan_pieces(tiles, pp);
-        if (!c->force_splits) { c->plan_key = key; c->plan_want = want; }
-      }
-    }
     if (chunked) {
-      // The layer was loaded in chunks of cb block indices: piece k of every tile covers the
-      // sub-tiles of chunk k and is launched behind that chunk's event; what is left (the end of
-      // the prefix that shares a sub-tile with the suffix, the suffix itself) is the last piece
-      // and waits for the whole layer.  groups[k] lists the work items of launch k.
-      groups.assign((size_t)nck + 1, {});
-      const int sub_per_chunk = cb / 2;
-      for (const Tile& t : tiles) {
-        const int full = reqs[t.req].n_prefix_blocks / 2;          // sub-tiles wholly inside the prefix
-        const int32_t first = (int32_t)items.size();
-        int n = 0;
-        for (int a = 0; a < full; a += sub_per_chunk) n++;
-        const int cut_end = std::min(full, n * sub_per_chunk);
-        const int total = n + (cut_end < t.n_sub ? 1 : 0);
-        if (total > 1) split_tiles.push_back(first);
-        for (int k = 0; k < n; k++) {
-          groups[(size_t)std::min(k, nck)].push_back((int32_t)items.size());
-          items.push_back({t.req, t.tile, k * sub_per_chunk, std::min(full, (k + 1) * sub_per_chunk), total, first, 0, 0});
-        }
-        if (cut_end < t.n_sub) {
-          groups[(size_t)nck].push_back((int32_t)items.size());
-          items.push_back({t.req, t.tile, cut_end, t.n_sub, total, first, 0, 0});
-        }
-      }
+      plan = plan_items_chunked(tiles, pblocks.data(), cb, nck);
     } else {
-      for (const Tile& t : tiles) {
-        const int len = piece_len(t.n_sub, want);
-        const int n = (t.n_sub + len - 1) / len;
-        const int32_t first = (int32_t)items.size();
-        if (n > 1) split_tiles.push_back(first);
-        for (int k = 0; k < n; k++)
-          items.push_back({t.req, t.tile, k * len, std::min(t.n_sub, (k + 1) * len), n, first, 0, 0});
+      int want = 1;
+      if (attn_mfma_splits_context(variant)) {
+        // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
+        // is kept for the following layers
+        std::vector<int64_t> key;
+        key.reserve(2 * n_reqs + 1);
+        key.push_back(variant);
+        for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
+        if (!c->force_splits && key == c->plan_key) want = c->plan_want;
+        else {
+          want = plan_pieces(tiles, pp);
+          if (!c->force_splits) { c->plan_key = key; c->plan_want = want; }
+        }
       }
+      plan = plan_items(tiles, want, pp);
     }
   }
+  const std::vector<WorkItem>& items = plan.items;
+  const std::vector<int32_t>& split_tiles = plan.split_tiles;
+  const std::vector<std::vector<int32_t>>& groups = plan.groups;
   const size_t items_off = blob.size();
   for (const WorkItem& it : items) {
     const int32_t* w = (const int32_t*)&it;

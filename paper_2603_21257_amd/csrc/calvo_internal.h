@@ -16,19 +16,6 @@ struct ReqDesc {
   int32_t q_off;      // first row of this request inside q / out / k_suffix / v_suffix
 };
 
-// One unit of attention work: a tile of suffix tokens of one request and a range of 32-key
-// sub-tiles of its context.  A tile whose context is cut into n_splits > 1 ranges produces partial
-// results (unnormalised O, running maximum, row sum) that merge_splits_kernel combines; the pieces
-// of one tile are consecutive work items.
-struct WorkItem {
-  int32_t req;
-  int32_t q_tile;     // tile index inside the request's suffix
-  int32_t sub_begin;  // first 32-key sub-tile of this piece
-  int32_t sub_end;    // one past its last sub-tile (the last piece ends at the tile's causal limit)
-  int32_t n_splits;   // pieces the tile is cut into; 1 = the kernel writes the final output itself
-  int32_t first_item; // index of the tile's first piece
-  int32_t pad0, pad1;
-};
 
 struct AttnParams {
   const void* q;
