@@ -601,6 +601,68 @@ int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int laye
   return CALVO_OK;
 }
 
+// What the attention kernels read besides Q and the pool, as one array of int32 (offsets in int32):
+// request descriptors (ReqDesc x n), work items, first items of the cut tiles, per-launch work item
+// lists, block tables, block byte offsets.  Each request's table is followed by copies of its last
+// entry (kTablePad of them, one more if that makes the count even) so that a kernel may look
+// kTablePad blocks past the end without clamping.  The offsets are slot * block_bytes (the byte
+// offset of the block inside a layer of the pool) for the same blocks, split by parity: first those
+// of blocks 0, 2, 4, ... then those of blocks 1, 3, 5, ... - a wave that always fetches the same
+// half of a 32-key sub-tile reads its offsets from consecutive addresses.
+struct BlobLayout {
+  size_t items_off = 0, split_off = 0, tables_off = 0, offs_off = 0;
+  std::vector<size_t> group_off;
+};
+
+BlobLayout build_descriptor_blob(const calvo_ctx* c, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix,
+                                 const PlanItems& plan, std::vector<int32_t>& blob) {
+  BlobLayout lay;
+  auto table_len = [&](int r) { return (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens; };
+  blob.clear();
+  blob.reserve(4 * n_reqs + 1024);
+  size_t n_tab = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = table_len(r);
+    blob.push_back((int32_t)n_tab);
+    blob.push_back(reqs[r].n_prefix_blocks * kBlockTokens);
+    blob.push_back(reqs[r].suffix_len);
+    blob.push_back(cu_suffix[r]);
+    n_tab += (size_t)nt + kTablePad + (nt & 1);
+  }
+  lay.items_off = blob.size();
+  for (const WorkItem& it : plan.items) {
+    const int32_t* w = (const int32_t*)&it;
+    blob.insert(blob.end(), w, w + sizeof(WorkItem) / 4);
+  }
+  lay.split_off = blob.size();
+  blob.insert(blob.end(), plan.split_tiles.begin(), plan.split_tiles.end());
+  for (const auto& g : plan.groups) {
+    lay.group_off.push_back(blob.size());
+    blob.insert(blob.end(), g.begin(), g.end());
+  }
+  lay.tables_off = blob.size();
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = table_len(r);
+    blob.insert(blob.end(), reqs[r].block_table, reqs[r].block_table + nt);
+    blob.insert(blob.end(), kTablePad + (nt & 1), nt > 0 ? reqs[r].block_table[nt - 1] : 0);
+  }
+  if (blob.size() & 1) blob.push_back(0);                       // 8-byte alignment of the offsets
+  lay.offs_off = blob.size();
+  size_t base = lay.tables_off;
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = table_len(r);
+    const size_t padded = (size_t)nt + kTablePad + (nt & 1);
+    for (int par = 0; par < 2; par++)
+      for (size_t i = par; i < padded; i += 2) {
+        const int64_t off = (int64_t)blob[base + i] * (int64_t)c->blk_bytes;
+        blob.push_back((int32_t)(uint32_t)(off & 0xffffffff));
+        blob.push_back((int32_t)(off >> 32));
+      }
+    base += padded;
+  }
+  return lay;
+}
+
 }  // namespace
 
 extern "C" {
@@ -917,24 +979,6 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
   const int tile_tokens = mfma ? attn_mfma_tile_tokens(variant, HW) : 1;
 
-  // ---- descriptor blob: requests, work items (heaviest first), block tables, block byte offsets.
-  // Each request's table is followed by copies of its last entry (kTablePad of them, one more if
-  // that makes the count even) so that a kernel may look kTablePad blocks past the end without
-  // clamping.  blk_offs holds slot * block_bytes (the byte offset of the block inside a layer of
-  // the pool) for the same blocks, split by parity: first the offsets of blocks 0, 2, 4, ... then
-  // those of blocks 1, 3, 5, ... - a wave that always fetches the same half of a 32-key sub-tile
-  // reads its offsets from consecutive addresses.
-  std::vector<int32_t> blob;
-  blob.reserve(4 * n_reqs + 1024);
-  size_t n_tab = 0;
-  for (int r = 0; r < n_reqs; r++) {
-    const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
-    blob.push_back((int32_t)n_tab);
-    blob.push_back(reqs[r].n_prefix_blocks * kBlockTokens);
-    blob.push_back(reqs[r].suffix_len);
-    blob.push_back(cu_suffix[r]);
-    n_tab += (size_t)nt + kTablePad + (nt & 1);
-  }
   // Work items: tiles of suffix tokens, heaviest first, each possibly cut into split-KV pieces
   // (consecutive work items) that the merge kernel combines; see attn_plan.cpp.
   PlanItems plan;
@@ -975,40 +1019,10 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const std::vector<WorkItem>& items = plan.items;
   const std::vector<int32_t>& split_tiles = plan.split_tiles;
   const std::vector<std::vector<int32_t>>& groups = plan.groups;
-  const size_t items_off = blob.size();
-  for (const WorkItem& it : items) {
-    const int32_t* w = (const int32_t*)&it;
-    blob.insert(blob.end(), w, w + sizeof(WorkItem) / 4);
-  }
-  const size_t split_off = blob.size();
-  blob.insert(blob.end(), split_tiles.begin(), split_tiles.end());
-  std::vector<size_t> group_off;
-  for (const auto& g : groups) {
-    group_off.push_back(blob.size());
-    blob.insert(blob.end(), g.begin(), g.end());
-  }
-  const size_t tables_off = blob.size();
-  for (int r = 0; r < n_reqs; r++) {
-    const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
-    blob.insert(blob.end(), reqs[r].block_table, reqs[r].block_table + nt);
-    blob.insert(blob.end(), kTablePad + (nt & 1), nt > 0 ? reqs[r].block_table[nt - 1] : 0);
-  }
-  if (blob.size() & 1) blob.push_back(0);                       // 8-byte alignment of the offsets
-  const size_t offs_off = blob.size();
-  {
-    size_t base = tables_off;
-    for (int r = 0; r < n_reqs; r++) {
-      const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
-      const size_t padded = (size_t)nt + kTablePad + (nt & 1);
-      for (int par = 0; par < 2; par++)
-        for (size_t i = par; i < padded; i += 2) {
-          const int64_t off = (int64_t)blob[base + i] * (int64_t)c->blk_bytes;
-          blob.push_back((int32_t)(uint32_t)(off & 0xffffffff));
-          blob.push_back((int32_t)(off >> 32));
-        }
-      base += padded;
-    }
-  }
+  std::vector<int32_t> blob;
+  const BlobLayout lay = build_descriptor_blob(c, reqs, n_reqs, cu_suffix, plan, blob);
+  const size_t items_off = lay.items_off, split_off = lay.split_off, tables_off = lay.tables_off, offs_off = lay.offs_off;
+  const std::vector<size_t>& group_off = lay.group_off;
 
   rc = ensure_att_blob(c, blob.size());
   if (rc != CALVO_OK) return rc;
