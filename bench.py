@@ -229,7 +229,8 @@ def main():
                 f"max {ks_sorted[-1]:.3f} ms; first step, layers 0-7: " + " ".join(f"{x:.3f}" for x in kern_ms[:8]))
         kernel_id, kernel_wgs = cb.calvo_attn_kernel_info(ctx, 0)
         ms = statistics.mean(step_ms)
-        k_ms = statistics.mean(kern_ms)
+        # every layer chunk-granular: no whole-layer launch inside the steps, take the launches of the attention-only pass
+        k_ms = statistics.mean(kern_ms) if kern_ms else t_att / L
         log("[bench] host time per step, warm-up steps first (ingest call, attention calls, final wait) ms: " +
             ", ".join("(%.2f %.2f %.2f)" % tuple(1e3 * x for x in t) for t in host_trace))
         flop_per_launch = w.attn_flop() / L
