@@ -1,6 +1,6 @@
 """Seeded random batches through the whole HIP path against the CPU oracle: head layouts,
 request counts, prefix / suffix lengths (empty, one token, ragged, partial last block),
-staging sizes, chunk-granular loading, the attention kernel and forced context splits drawn at random.  Every case is valid input; pool
+staging sizes, chunk-granular loading, the softmax scale, the attention kernel and forced context splits drawn at random.  Every case is valid input; pool
 bytes must be bit exact and attention within the bf16 tolerance."""
 import numpy as np
 import pytest
@@ -34,6 +34,8 @@ def draw_case(seed):
         kw["n_staging"] = int(rng.choice([2, 3]))
     if rng.integers(0, 2):
         kw["chunk_blocks"] = [int(2 * rng.integers(0, 17)) for _ in range(n_layers)]     # 0 = that layer as a whole
+    if rng.integers(0, 3) == 0:
+        kw["scale"] = float(rng.choice([0.03, 0.2]))                 # explicit softmax scale instead of 1 / sqrt(D)
     env = {}
     pick = int(rng.integers(0, 4))
     if pick == 1:
@@ -51,6 +53,6 @@ def test_random_batch(seed, monkeypatch):
     w = wl.make_custom(shape, lens, seed=9000 + seed, shared_blocks=shared)
     print(f"[case] seed={seed} shape={shape} lens={lens} shared={shared} kw={kw} env={env}", flush=True)
     pool_g, out_g = hh.run_hip(w, **kw)
-    pool_o, out_o = hh.run_oracle(w)
+    pool_o, out_o = hh.run_oracle(w, scale=kw.get("scale"))
     hh.assert_pool_bit_exact(pool_g, pool_o)
     hh.assert_attn_close(out_g, out_o, "bf16")
