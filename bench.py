@@ -120,8 +120,8 @@ def main():
     del probe_dst
     log(f"[bench] measured pinned H2D peak {h2d_peak:.2f} GB/s")
 
-    if args.staging_mib < 0:      # one copy-engine transfer per layer: fewest gaps on the PCIe link
-        args.staging_mib = max(1, min(512, -(-w.ingest_bytes() // L // (1 << 20))))
+    if args.staging_mib < 0:      # one copy-engine transfer per layer (several small layers per transfer): fewest gaps on the PCIe link
+        args.staging_mib = max(256, min(512, -(-w.ingest_bytes() // L // (1 << 20))))
     stride = w.host_blocks * s.blk_bytes
     reqs = [cb.make_request(host.data_ptr() + r.host_block_start * s.blk_bytes, stride, r.table,
                             r.n_prefix_blocks, r.suffix_len, r.first_ingest_block) for r in w.requests]

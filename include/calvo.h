@@ -39,7 +39,9 @@
  * cuts every attention tile's context into n pieces; CALVO_SPLIT_MIN,
  * CALVO_SPLIT_FILL = parameters of the automatic cut (shortest piece, cost of
  * a workgroup's start and end, both in 32-key steps); CALVO_SCATTER_GRID =
- * workgroups of the zero-copy scatter.  Read by every calvo_prefill_attn:
+ * workgroups of the zero-copy scatter; CALVO_MERGE_MIB = most bytes of
+ * consecutive small layers that one transfer carries (default 256, 0 = every
+ * layer by itself).  Read by every calvo_prefill_attn:
  * CALVO_ATTN_VARIANT = 3 or 4 forces the 8-wave or the 4-wave bf16 kernel
  * (other values 0-2: the unpipelined comparison kernels).
  */
@@ -108,7 +110,12 @@ int calvo_destroy(calvo_ctx* ctx);
  *     pool[l][block_table[j]]  <-  host block j of layer l        (raw bytes, bit exact)
  * No other pool byte is written.  Asynchronous: the call queues copy-engine transfers into
  * the staging ring and scatter kernels on internal streams, records layer l's event after
- * the last store of layer l, and returns.  Layers are issued in ascending order.
+ * the last store of layer l, and returns.  Layers are issued in ascending order.  When the
+ * loaded blocks of consecutive layers follow each other in host memory and several such
+ * layers fit one staging buffer, up to 256 MiB of them cross PCIe as one transfer (every
+ * transfer boundary costs link time): groups of 1, 2, 4 ... layers, shrinking again towards
+ * layer_end so that the last layers travel alone; each layer keeps its own scatter and
+ * event, which fires once its group has landed.
  * Errors (nothing queued): CALVO_EINVAL for NULL pointers, a layer range outside
  * [0, n_layers], slot ids outside the pool or repeated inside one request, negative counts,
  * first_ingest_block > n_prefix_blocks, a host_layer_stride smaller than the request's

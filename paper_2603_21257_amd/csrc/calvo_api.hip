@@ -88,6 +88,7 @@ struct calvo_ctx {
   std::vector<char> timed;
   std::vector<int32_t> last_variant, last_wgs;   // per layer: attention kernel chosen, workgroups launched
   int scatter_grid = 64;
+  size_t merge_bytes = (size_t)256 << 20;   // consecutive small layers cross PCIe together up to this size (CALVO_MERGE_MIB)
   int force_splits = 0;           // CALVO_ATTN_SPLITS: pieces per tile (0 = automatic)
   int split_min = 48;             // shortest piece of a cut tile, in 32-key sub-tiles
   int split_fill = 30;            // cost of a workgroup's pipeline fill and drain, in sub-tile steps (launch replay)
@@ -242,6 +243,7 @@ int ensure_att_blob(calvo_ctx* c, size_t n) {
 // pools start with room for the short-query batches (kPartialSlots0), so only long chunk-granular
 // layers ever grow it.
 constexpr size_t kPartialSlots0 = 4096;      // 68 MB
+
 int ensure_partials(calvo_ctx* c, size_t slots) {
   if (slots <= c->part_slots) return CALVO_OK;
   if (c->part_slots) HIP_TRY(hipStreamSynchronize(c->s_compute));
@@ -472,6 +474,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   }
   if (const char* e = getenv("CALVO_SPLIT_MIN")) { const int g = atoi(e); if (g >= 1 && g <= 4096) c->split_min = g; }
   if (const char* e = getenv("CALVO_SPLIT_FILL")) { const int g = atoi(e); if (g >= 0 && g <= 4096) c->split_fill = g; }
+  if (const char* e = getenv("CALVO_MERGE_MIB")) { const int g = atoi(e); if (g >= 0 && g <= 4096) c->merge_bytes = (size_t)g << 20; }
   if (const char* e = getenv("CALVO_SCATTER_GRID")) {   // tuning knob: workgroups of the zero-copy scatter
     const int g = atoi(e);
     if (g >= 1 && g <= 4096) c->scatter_grid = g;
@@ -703,37 +706,49 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
     return CALVO_OK;
   };
 
-  for (int l = layer_begin; l < layer_end; l++) {
-    const int64_t cb = chunk_blocks ? chunk_blocks[l - layer_begin] : 0;
-    const int64_t nck = cb > 0 ? (max_blocks + cb - 1) / cb : 0;
-    if (nck > 0) {
-      // events of this layer's chunks (kept for later calls)
-      while ((int64_t)c->ev_chunk[l].size() < nck) {
+  // Requests whose host blocks (and hence table entries) follow each other load as one run: every
+  // transfer boundary costs PCIe time.  A run = blocks [j0, j1) in request r's numbering, continued
+  // through the requests that follow it.
+  struct Run { int r; int64_t j0, j1; const unsigned char* beg; };
+  auto layer_runs = [&](int l) {
+    std::vector<Run> runs;
+    for (int r = 0; r < n_reqs;) {
+      if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) { r++; continue; }
+      int64_t j1 = reqs[r].n_prefix_blocks;
+      int r2 = r + 1;
+      for (; r2 < n_reqs; r2++) {
+        const calvo_request& a = reqs[r], &b = reqs[r2];
+        if (b.n_prefix_blocks == b.first_ingest_block) continue;
+        const unsigned char* end = src[r] + (int64_t)l * a.host_layer_stride + j1 * (int64_t)c->blk_bytes;
+        const unsigned char* beg = src[r2] + (int64_t)l * b.host_layer_stride + b.first_ingest_block * (int64_t)c->blk_bytes;
+        if (end != beg || tab_off[r] + j1 != tab_off[r2] + b.first_ingest_block) break;
+        j1 += b.n_prefix_blocks - b.first_ingest_block;
+      }
+      const int64_t j0 = reqs[r].first_ingest_block;
+      runs.push_back({r, j0, j1, src[r] + (int64_t)l * reqs[r].host_layer_stride + j0 * (int64_t)c->blk_bytes});
+      r = r2;
+    }
+    return runs;
+  };
+  auto chunk_of = [&](int l) -> int64_t { return chunk_blocks ? chunk_blocks[l - layer_begin] : 0; };
+  auto mark_issued = [&](int l, int64_t cb, int64_t nck) {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->layer_issued[l] = 1;
+    c->chunk_blocks[l] = (int32_t)cb;
+    c->n_chunks[l] = (int32_t)nck;
+    c->chunks_issued[l] = (int32_t)nck;
+  };
+
+  int group = 0;                       // whole-layer transfers issued so far (sets the merge ramp)
+  for (int l = layer_begin; l < layer_end;) {
+    const int64_t cb = chunk_of(l);
+    if (cb > 0) {
+      const int64_t nck = (max_blocks + cb - 1) / cb;
+      while ((int64_t)c->ev_chunk[l].size() < nck) {       // events of this layer's chunks (kept for later calls)
         hipEvent_t ev = nullptr;
         HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
         c->ev_chunk[l].push_back(ev);
       }
-    }
-    if (cb == 0) {
-      // requests whose host blocks (and hence table entries) follow each other load as one run:
-      // every transfer boundary costs PCIe time
-      for (int r = 0; r < n_reqs;) {
-        if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) { r++; continue; }
-        int64_t j1 = reqs[r].n_prefix_blocks;
-        int r2 = r + 1;
-        for (; r2 < n_reqs; r2++) {
-          const calvo_request& a = reqs[r], &b = reqs[r2];
-          if (b.n_prefix_blocks == b.first_ingest_block) continue;
-          const unsigned char* end = src[r] + (int64_t)l * a.host_layer_stride + j1 * (int64_t)c->blk_bytes;
-          const unsigned char* beg = src[r2] + (int64_t)l * b.host_layer_stride + b.first_ingest_block * (int64_t)c->blk_bytes;
-          if (end != beg || tab_off[r] + j1 != tab_off[r2] + b.first_ingest_block) break;
-          j1 += b.n_prefix_blocks - b.first_ingest_block;     // continue request r's block numbering through b
-        }
-        rc = load_range(l, r, reqs[r].first_ingest_block, j1);
-        if (rc != CALVO_OK) return rc;
-        r = r2;
-      }
-    } else {
       // chunk k = block indices [k cb, (k+1) cb) of every request (a shared run sits at the same
       // indices in every table, so once chunk k is in, all blocks below (k+1) cb are resident)
       for (int64_t k = 0; k < nck; k++) {
@@ -744,13 +759,61 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
         }
         HIP_TRY(hipEventRecord(c->ev_chunk[l][k], c->s_scatter));
       }
+      HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
+      mark_issued(l, cb, nck);
+      l++;
+      continue;
     }
-    HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
-    std::lock_guard<std::mutex> lk(c->mu);
-    c->layer_issued[l] = 1;
-    c->chunk_blocks[l] = (int32_t)cb;
-    c->n_chunks[l] = (int32_t)nck;
-    c->chunks_issued[l] = (int32_t)nck;
+    const std::vector<Run> runs = layer_runs(l);
+    // Small layers: when a layer is one run and the next layers' runs follow it in host memory, up
+    // to merge_bytes of consecutive layers cross PCIe as one transfer (then one scatter and one event
+    // per layer).  The group size ramps up 1, 2, 4, ... so the first layer still arrives at once, and
+    // stays within a third of the layers still to come (rounded up), so the groups shrink towards the
+    // end of the call and the last layers travel alone: the attention of a group's layers can only
+    // start when the whole group is in, and must not pile up behind the last transfer (it does not
+    // as long as a layer's attention takes at most two thirds of its load; slower attention bounds
+    // the step anyway).
+    int k = 1;
+    if (c->n_staging > 0 && runs.size() == 1) {
+      const int64_t nb = runs[0].j1 - runs[0].j0;
+      const int64_t fit = std::min<int64_t>(c->staging_blocks / nb, (int64_t)(c->merge_bytes / ((size_t)nb * c->blk_bytes)));
+      const int64_t kmax = std::min<int64_t>({fit, (int64_t)1 << std::min(group, 16), ((int64_t)layer_end - l + 2) / 3});
+      while (k < kmax && chunk_of(l + k) == 0) {
+        const std::vector<Run> next = layer_runs(l + k);
+        if (next.size() != 1 || next[0].r != runs[0].r || next[0].j0 != runs[0].j0 || next[0].j1 != runs[0].j1 ||
+            next[0].beg != runs[0].beg + (int64_t)k * nb * (int64_t)c->blk_bytes)
+          break;
+        k++;
+      }
+    }
+    if (k > 1) {
+      const Run& u = runs[0];
+      const int64_t nb = u.j1 - u.j0;
+      const size_t run_bytes = (size_t)nb * c->blk_bytes;
+      const int b = (int)(c->seq % (uint64_t)c->n_staging);
+      hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
+      if (c->free_recorded[b]) HIP_TRY(hipStreamWaitEvent(cs, c->ev_free[b], 0));
+      HIP_TRY(hipMemcpyAsync(c->staging[b], u.beg, (size_t)k * run_bytes, hipMemcpyHostToDevice, cs));
+      HIP_TRY(hipEventRecord(c->ev_filled[b], cs));
+      HIP_TRY(hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0));
+      for (int i = 0; i < k; i++) {
+        unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)(l + i) * c->layer_bytes;
+        HIP_TRY(launch_scatter_blocks((const unsigned char*)c->staging[b] + (size_t)i * run_bytes, pool_layer,
+                                      c->d_tab_ing + tab_off[u.r] + u.j0, nb, (int32_t)c->blk_bytes, 1024, c->s_scatter));
+        HIP_TRY(hipEventRecord(c->ev_layer[l + i], c->s_scatter));
+        mark_issued(l + i, 0, 0);
+      }
+      HIP_TRY(hipEventRecord(c->ev_free[b], c->s_scatter));
+      c->free_recorded[b] = 1;
+      c->seq++;
+    } else {
+      for (const Run& u : runs)
+        if ((rc = load_range(l, u.r, u.j0, u.j1)) != CALVO_OK) return rc;
+      HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
+      mark_issued(l, 0, 0);
+    }
+    group++;
+    l += k;
   }
   return CALVO_OK;
 }

@@ -134,6 +134,21 @@ def test_staged_copy_engine_ingest_is_bit_exact(staging_blocks, n_staging, n_cop
     check(w, staging_bytes=staging_blocks * shape.blk_bytes, n_staging=n_staging, n_copy_streams=n_copy)
 
 
+@pytest.mark.parametrize("n_layers,lens,shared,staging_blocks", [
+    (6, [(160, 40)], 0, 64),                               # groups of 1, 2, 1, 1, 1 layers
+    (9, [(96, 20)], 0, 200),                               # 1, 2, 2, 2, 1, 1
+    (12, [(64, 10), (128, 33), (96, 5)], 2, 64),           # a batch that loads as one run per layer: 1, 2, 3, 2, 2, 1, 1
+    (5, [(160, 40)], 0, 15),                               # staging holds one layer and a half: no merge
+])
+def test_small_layers_share_a_transfer(n_layers, lens, shared, staging_blocks):
+    """Layers that are one run each and follow each other in host memory cross PCIe together when
+    the staging buffer holds several of them; every layer still gets its own scatter and event."""
+    need = sum(p // 16 + -(-s // 16) for p, s in lens) - shared * (len(lens) - 1)
+    shape = wl.Shape(n_layers, 8, 2, 128, "bf16", need + 20)
+    w = wl.make_custom(shape, lens, seed=31 * n_layers + staging_blocks, shared_blocks=shared)
+    check(w, staging_bytes=staging_blocks * shape.blk_bytes, n_staging=2)
+
+
 @pytest.mark.parametrize("order", ["as laid out", "reversed", "interleaved"])
 @pytest.mark.parametrize("staging_blocks", [0, 7, 64])
 def test_batch_ingest_in_any_request_order(order, staging_blocks):
