@@ -307,3 +307,40 @@ def test_attention_waits_for_ingest_of_its_layer():
     for l in (0, 5):
         want = hh.orc.prefill_attn_sampled(view[l], w.q[l], r.table, r.prefix_len, r.suffix_len, B, rows)
         hh.assert_attn_close(out_g[l][rows], want, "bf16")
+
+
+def test_caller_owned_compute_stream_orders_the_output():
+    """With a caller's stream as the compute stream, work queued on that stream after
+    calvo_prefill_attn sees the finished output (no host synchronisation in between), the inputs may
+    be produced on that stream right before the call, and calvo_destroy leaves the stream usable."""
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 96)
+    w = wl.make_custom(shape, [(512, 90), (256, 33)], seed=77)
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(shape), shape, dev)
+    host = hh.to_torch(w.host_kv, shape, pin=True)
+    q_src, ks_src, vs_src = (hh.to_torch(a, shape, dev) for a in (w.q, w.k_suffix, w.v_suffix))
+    T = w.total_suffix
+    out = torch.full((3, T, 8, 128), float("nan"), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    ctx = cb.calvo_create(3, 8, 2, 128, cb.CALVO_BF16, 96, pool, staging_bytes=8 * shape.blk_bytes,
+                          compute_stream=st.cuda_stream)
+    snaps = []
+    try:
+        reqs = hh.make_requests(w, host)
+        cb.calvo_kv_ingest(ctx, reqs, 0, 3)
+        with torch.cuda.stream(st):
+            for l in range(3):
+                q, ks, vs = q_src[l].clone(), ks_src[l].clone(), vs_src[l].clone()     # produced on the stream, just before
+                cb.calvo_prefill_attn(ctx, l, q, ks, vs, out[l], reqs, w.cu_suffix, 0.0)
+                snaps.append(out[l].clone())                                           # consumed on the stream, right after
+        st.synchronize()
+        got = torch.stack(snaps)
+    finally:
+        cb.calvo_destroy(ctx)
+    with torch.cuda.stream(st):                     # the stream is the caller's: still there
+        again = got.float().sum()
+    st.synchronize()
+    assert torch.isfinite(again)
+    _, out_o = hh.run_oracle(w)
+    hh.assert_attn_close(hh.to_numpy_stored(got, shape), out_o, "bf16")
