@@ -322,6 +322,20 @@ int calvo_pool_cancel(calvo_pool* pool, int64_t ticket);
  * stream).  Blocks until that kernel has finished.  CALVO_ENOTREADY if none was queued. */
 int calvo_attn_kernel_ms(calvo_ctx* ctx, int layer, float* ms);
 
+/* Planning helper (host code, needs no GPU; host_kv is only used as an address): how
+ * calvo_kv_ingest / calvo_kv_ingest_chunked would move layers [layer_begin, layer_end) of these
+ * requests across PCIe with staging buffers of staging_blocks blocks of block_bytes bytes (0 = the
+ * zero-copy mode) and at most merge_bytes per shared transfer (the library's default is 256 MiB).
+ * chunk_blocks: NULL, or layer_end - layer_begin chunk sizes as for calvo_kv_ingest_chunked.
+ * Outputs, HOST arrays of layer_end - layer_begin int32, either may be NULL:
+ * transfer_of_layer[i] = index of the whole-layer transfer group that carries layer layer_begin + i
+ * (layers with the same index share one transfer; -1 for a layer loaded in chunks), runs_of_layer[i] =
+ * number of runs of consecutive host blocks the layer consists of (each run is a transfer of its
+ * own, cut further where it exceeds a staging buffer).  CALVO_EINVAL for bad arguments. */
+int calvo_ingest_plan(const calvo_request* reqs, int32_t n_reqs, int32_t layer_begin, int32_t layer_end,
+                      int64_t block_bytes, int64_t staging_blocks, int64_t merge_bytes, const int32_t* chunk_blocks,
+                      int32_t* transfer_of_layer, int32_t* runs_of_layer);
+
 /* Planning helper (host code, needs no GPU): what calvo_prefill_attn would launch for a bf16, head
  * dim 128 batch with these lengths on a device with n_cus compute units.  prefix_blocks / suffix_lens:
  * HOST arrays of n_reqs.  Outputs (any may be NULL): *kernel as in calvo_attn_kernel_info,

@@ -22,7 +22,7 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
            "calvo_pool_cancel", "calvo_last_error"]
@@ -96,6 +96,8 @@ def lib() -> C.CDLL:
                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.calvo_attn_plan_items.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                             C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32)]
+        L.calvo_ingest_plan.argtypes = [C.POINTER(calvo_request), C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                        C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.calvo_attn_kernel_info.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         dp = C.POINTER(C.c_double)
         L.calvo_cost_fit.argtypes = [dp, dp, C.c_int, dp, dp]
@@ -322,6 +324,24 @@ def calvo_attn_plan_items(n_q_heads: int, n_kv_heads: int, n_cus: int, prefix_bl
         if rc != CALVO_OK:
             raise CalvoError(rc, "invalid planning argument")
     return out
+
+
+def calvo_ingest_plan(reqs, layer_begin: int, layer_end: int, block_bytes: int, staging_blocks: int,
+                      merge_bytes: int = 256 << 20, chunk_blocks=None):
+    """(transfer group of every layer, runs of every layer) as the ingest calls would move them; reqs as for calvo_kv_ingest."""
+    n = layer_end - layer_begin
+    arr = _req_array(reqs)
+    i32p = C.POINTER(C.c_int32)
+    cbk = None if chunk_blocks is None else np.ascontiguousarray(chunk_blocks, dtype=np.int32)
+    if cbk is not None and len(cbk) != n:
+        raise ValueError("chunk_blocks needs one entry per layer")
+    groups, runs = np.zeros(max(n, 1), np.int32), np.zeros(max(n, 1), np.int32)
+    rc = lib().calvo_ingest_plan(arr, len(reqs), layer_begin, layer_end, block_bytes, staging_blocks, merge_bytes,
+                                 None if cbk is None else cbk.ctypes.data_as(i32p), groups.ctypes.data_as(i32p),
+                                 runs.ctypes.data_as(i32p))
+    if rc != CALVO_OK:
+        raise CalvoError(rc, "invalid planning argument")
+    return groups[:n], runs[:n]
 
 
 def calvo_attn_kernel_info(ctx: int, layer: int):

@@ -18,6 +18,7 @@
 
 #include "../../include/calvo.h"
 #include "calvo_internal.h"
+#include "ingest_plan.h"
 
 using namespace calvo;
 
@@ -706,30 +707,12 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
     return CALVO_OK;
   };
 
-  // Requests whose host blocks (and hence table entries) follow each other load as one run: every
-  // transfer boundary costs PCIe time.  A run = blocks [j0, j1) in request r's numbering, continued
-  // through the requests that follow it.
-  struct Run { int r; int64_t j0, j1; const unsigned char* beg; };
-  auto layer_runs = [&](int l) {
-    std::vector<Run> runs;
-    for (int r = 0; r < n_reqs;) {
-      if (reqs[r].n_prefix_blocks == reqs[r].first_ingest_block) { r++; continue; }
-      int64_t j1 = reqs[r].n_prefix_blocks;
-      int r2 = r + 1;
-      for (; r2 < n_reqs; r2++) {
-        const calvo_request& a = reqs[r], &b = reqs[r2];
-        if (b.n_prefix_blocks == b.first_ingest_block) continue;
-        const unsigned char* end = src[r] + (int64_t)l * a.host_layer_stride + j1 * (int64_t)c->blk_bytes;
-        const unsigned char* beg = src[r2] + (int64_t)l * b.host_layer_stride + b.first_ingest_block * (int64_t)c->blk_bytes;
-        if (end != beg || tab_off[r] + j1 != tab_off[r2] + b.first_ingest_block) break;
-        j1 += b.n_prefix_blocks - b.first_ingest_block;
-      }
-      const int64_t j0 = reqs[r].first_ingest_block;
-      runs.push_back({r, j0, j1, src[r] + (int64_t)l * reqs[r].host_layer_stride + j0 * (int64_t)c->blk_bytes});
-      r = r2;
-    }
-    return runs;
-  };
+  // Requests whose host blocks (and hence table entries) follow each other load as one run, and
+  // consecutive small layers share a transfer: see ingest_plan.cpp.
+  std::vector<IngestSrc> isrc((size_t)n_reqs);
+  for (int r = 0; r < n_reqs; r++)
+    isrc[(size_t)r] = {(uintptr_t)src[r], reqs[r].host_layer_stride, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks,
+                       tab_off[r]};
   auto chunk_of = [&](int l) -> int64_t { return chunk_blocks ? chunk_blocks[l - layer_begin] : 0; };
   auto mark_issued = [&](int l, int64_t cb, int64_t nck) {
     std::lock_guard<std::mutex> lk(c->mu);
@@ -764,36 +747,17 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
       l++;
       continue;
     }
-    const std::vector<Run> runs = layer_runs(l);
-    // Small layers: when a layer is one run and the next layers' runs follow it in host memory, up
-    // to merge_bytes of consecutive layers cross PCIe as one transfer (then one scatter and one event
-    // per layer).  The group size ramps up 1, 2, 4, ... so the first layer still arrives at once, and
-    // stays within a third of the layers still to come (rounded up), so the groups shrink towards the
-    // end of the call and the last layers travel alone: the attention of a group's layers can only
-    // start when the whole group is in, and must not pile up behind the last transfer (it does not
-    // as long as a layer's attention takes at most two thirds of its load; slower attention bounds
-    // the step anyway).
-    int k = 1;
-    if (c->n_staging > 0 && runs.size() == 1) {
-      const int64_t nb = runs[0].j1 - runs[0].j0;
-      const int64_t fit = std::min<int64_t>(c->staging_blocks / nb, (int64_t)(c->merge_bytes / ((size_t)nb * c->blk_bytes)));
-      const int64_t kmax = std::min<int64_t>({fit, (int64_t)1 << std::min(group, 16), ((int64_t)layer_end - l + 2) / 3});
-      while (k < kmax && chunk_of(l + k) == 0) {
-        const std::vector<Run> next = layer_runs(l + k);
-        if (next.size() != 1 || next[0].r != runs[0].r || next[0].j0 != runs[0].j0 || next[0].j1 != runs[0].j1 ||
-            next[0].beg != runs[0].beg + (int64_t)k * nb * (int64_t)c->blk_bytes)
-          break;
-        k++;
-      }
-    }
+    const std::vector<IngestRun> runs = ingest_layer_runs(isrc.data(), n_reqs, l, c->blk_bytes);
+    const int k = ingest_group_layers(isrc.data(), n_reqs, l, layer_end, chunk_blocks, layer_begin, c->blk_bytes,
+                                      c->n_staging > 0 ? c->staging_blocks : 0, c->merge_bytes, group);
     if (k > 1) {
-      const Run& u = runs[0];
+      const IngestRun& u = runs[0];
       const int64_t nb = u.j1 - u.j0;
       const size_t run_bytes = (size_t)nb * c->blk_bytes;
       const int b = (int)(c->seq % (uint64_t)c->n_staging);
       hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
       if (c->free_recorded[b]) HIP_TRY(hipStreamWaitEvent(cs, c->ev_free[b], 0));
-      HIP_TRY(hipMemcpyAsync(c->staging[b], u.beg, (size_t)k * run_bytes, hipMemcpyHostToDevice, cs));
+      HIP_TRY(hipMemcpyAsync(c->staging[b], (const void*)u.beg, (size_t)k * run_bytes, hipMemcpyHostToDevice, cs));
       HIP_TRY(hipEventRecord(c->ev_filled[b], cs));
       HIP_TRY(hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0));
       for (int i = 0; i < k; i++) {
@@ -807,7 +771,7 @@ static int ingest_impl(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
       c->free_recorded[b] = 1;
       c->seq++;
     } else {
-      for (const Run& u : runs)
+      for (const IngestRun& u : runs)
         if ((rc = load_range(l, u.r, u.j0, u.j1)) != CALVO_OK) return rc;
       HIP_TRY(hipEventRecord(c->ev_layer[l], c->s_scatter));
       mark_issued(l, 0, 0);
