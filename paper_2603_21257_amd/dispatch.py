@@ -94,3 +94,49 @@ def serve_trace_pooled(policy: int, model: Optional[Sequence[float]], jobs: Sequ
     for _, table in holders:
         cb.calvo_pool_release(pool, table)
     return start, finish, reactive, alloc_wait
+
+
+def serve_trace_two_stage(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
+                          try_issue: Callable[[int], bool], load_done: Callable[[int], bool],
+                          finished: Callable[[int], bool], clock: Callable[[], float] = time.perf_counter,
+                          sleep: Callable[[float], None] = time.sleep, poll_s: float = 1e-4):
+    """Loading and computation as two stages that progress on their own (paper Section 3.1): the loading
+    stage takes the next request - the policy's pick among those that have arrived - as soon as the
+    previous request's blocks are all loaded, while that request (and earlier ones) may still be
+    computing; computation follows in the order of loading.
+
+    try_issue(i) queues request i's loading and computation without waiting for either and returns
+    True, or returns False if it cannot be queued yet (no room for its blocks: it is tried again);
+    load_done(i) tells whether all of i's blocks are loaded; finished(i) whether its first token is
+    ready.  Returns (start_s, finish_s) as serve_trace does; a finish time is taken when the loop
+    notices it (every poll_s while it idles).
+    """
+    n = len(jobs)
+    issued = [False] * n
+    start, finish = [0.0] * n, [0.0] * n
+    in_flight = []
+    loading = -1
+    n_done = 0
+    t0 = clock()
+    while n_done < n:
+        now = clock() - t0
+        for i in list(in_flight):
+            if finished(i):
+                finish[i] = now
+                in_flight.remove(i)
+                n_done += 1
+        if loading >= 0 and load_done(loading):
+            loading = -1
+        if loading < 0 and not all(issued):
+            i = cb.calvo_sched_pick(policy, model, jobs, issued, now)
+            if i >= 0 and try_issue(i):
+                start[i] = now
+                issued[i] = True
+                loading = i
+                in_flight.append(i)
+                continue
+            if i < 0 and not in_flight:
+                sleep(max(0.0, min(jobs[k][0] for k in range(n) if not issued[k]) - now))
+                continue
+        sleep(poll_s)
+    return start, finish

@@ -117,6 +117,87 @@ class Server:
         return (la, lb, ca, cbb)
 
 
+class PipelinedServer(Server):
+    """The same path with several requests in flight: a request's blocks get slots of their own from
+    the slot allocator (paper Section 3.1, allocation at the moment loading is issued), loading and
+    attention are queued without waiting, and the next request's loading starts while this one still
+    computes.  The compute stream is the caller's, so a request's completion can be polled."""
+
+    def __init__(self, n_layers=8, seed=7, max_query=MAX_QRY, depth=4):
+        import torch
+        self.torch = torch
+        self.L, self.Hq, self.Hkv, self.D = n_layers, 32, 8, 128
+        self.max_query = max_query
+        per_req = (MAX_CTX + max_query) // 16 + 1
+        slots = depth * per_req
+        self.shape = s = wl.Shape(self.L, self.Hq, self.Hkv, self.D, "bf16", slots)
+        dev = torch.device("cuda:0")
+        self.host_blocks = MAX_CTX // 16
+        self.arena = hostmem.PinnedBuffer(self.L * self.host_blocks * s.blk_bytes)
+        self.host = wl.fill_normal_(self.arena.tensor((self.L, self.host_blocks, s.blk_elems), torch.bfloat16), seed)
+        self.pool = torch.empty((self.L, slots, s.blk_elems), dtype=torch.bfloat16, device=dev)
+        mk = lambda h, sd: wl.fill_normal_(torch.empty((self.L, max_query, h, self.D), dtype=torch.bfloat16, device=dev), sd)
+        self.q, self.ks, self.vs = mk(self.Hq, seed + 1), mk(self.Hkv, seed + 2), mk(self.Hkv, seed + 3)
+        self.outs = [torch.empty((self.L, max_query, self.Hq, self.D), dtype=torch.bfloat16, device=dev) for _ in range(depth)]
+        self.out = self.outs[0]
+        self.table = np.arange(per_req, dtype=np.int32)          # Server's single-request calls (profiling) use the first region
+        self.stream = torch.cuda.Stream()
+        self.ctx = cb.calvo_create(self.L, self.Hq, self.Hkv, self.D, cb.CALVO_BF16, slots, self.pool,
+                                   staging_bytes=256 << 20, compute_stream=self.stream.cuda_stream)
+        self.slots = cb.calvo_pool_create(slots)
+        self.flight = {}                                         # request -> (table, done event, out index)
+        self.free_outs = list(range(depth))
+        self.last_issued = -1
+
+    def close(self):
+        if self.slots:
+            cb.calvo_pool_destroy(self.slots)
+            self.slots = 0
+        super().close()
+
+    def try_issue(self, i, ctx_tokens, qry_tokens):
+        nb = ctx_tokens // 16 + -(-qry_tokens // 16)
+        if not self.free_outs or cb.calvo_pool_counts(self.slots)["free"] < nb:
+            return False
+        table = cb.calvo_pool_reserve(self.slots, nb)
+        o = self.free_outs.pop()
+        stride = self.host_blocks * self.shape.blk_bytes
+        r = cb.make_request(self.host.data_ptr(), stride, table, ctx_tokens // 16, qry_tokens)
+        cu = np.array([0, qry_tokens], np.int32)
+        cb.calvo_kv_ingest(self.ctx, [r], 0, self.L)
+        out = self.outs[o]
+        for l in range(self.L):
+            cb.calvo_prefill_attn(self.ctx, l, self.q[l, :qry_tokens], self.ks[l, :qry_tokens], self.vs[l, :qry_tokens],
+                                  out[l, :qry_tokens], [r], cu, 0.0)
+        ev = self.torch.cuda.Event()
+        ev.record(self.stream)
+        self.flight[i] = (table, ev, o)
+        self.last_issued = i
+        return True
+
+    def load_done(self, i):
+        # only asked about the request issued last: the per-layer events belong to the latest loading call
+        assert i == self.last_issued
+        return cb.calvo_layer_event(self.ctx, self.L - 1, cb.CALVO_EV_QUERY)
+
+    def finished(self, i):
+        table, ev, o = self.flight[i]
+        if not ev.query():
+            return False
+        cb.calvo_pool_release(self.slots, table)
+        self.free_outs.append(o)
+        del self.flight[i]
+        return True
+
+    def compute_only(self, ctx_tokens, qry_tokens):
+        super().compute_only(ctx_tokens, qry_tokens)
+        self.stream.synchronize()
+
+    def serve(self, ctx_tokens, qry_tokens):
+        super().serve(ctx_tokens, qry_tokens)
+        self.stream.synchronize()
+
+
 def make_jobs(lengths, model, load, seed):
     """Poisson arrivals at `load` times the server's capacity for these requests (1 = as fast as it can
     serve them on average); deadline = arrival + model TTFT x {2, 4, 8}."""
@@ -153,13 +234,55 @@ def study(n_requests=48, load=1.2, seed=1, n_layers=8, log=print):
         srv.close()
 
 
+def study_two_stage(n_requests=48, load=1.2, seed=1, n_layers=8, max_query=MAX_QRY, policies=POLICIES, log=print):
+    """The same trace on the pipelined server, once request by request (serve_trace) and once with
+    loading and computation as two stages (serve_trace_two_stage).
+    {policy: dict(serial mean TTFT s, two-stage mean TTFT s, deadlines met by each)} and the model."""
+    srv = PipelinedServer(n_layers, max_query=max_query)
+    try:
+        model = srv.fit_model()
+        log(f"fitted cost model: load {model[0] * 1e6:.3f} us/token + {model[1] * 1e3:.3f} ms, "
+            f"compute {model[2] * 1e6:.3f} us/token + {model[3] * 1e3:.3f} ms")
+        rng = np.random.default_rng(seed)
+        lengths = [(c, int(rng.integers(16, max_query + 1))) for c, _ in draw_lengths(rng, n_requests)]
+        jobs = make_jobs(lengths, model, load, seed + 1)
+        arr = np.array([j[0] for j in jobs])
+        ddl = np.array([j[1] for j in jobs])
+        res = {}
+        for name, pol in policies:
+            _, fin1 = dispatch.serve_trace(pol, model, jobs, lambda i: srv.serve(jobs[i][2], jobs[i][3]))
+            _, fin2 = dispatch.serve_trace_two_stage(pol, model, jobs, lambda i: srv.try_issue(i, jobs[i][2], jobs[i][3]),
+                                                     srv.load_done, srv.finished)
+            fin1, fin2 = np.array(fin1), np.array(fin2)
+            res[name] = {"serial_ttft_s": float(np.mean(fin1 - arr)), "two_stage_ttft_s": float(np.mean(fin2 - arr)),
+                         "serial_met": float(np.mean(fin1 <= ddl)), "two_stage_met": float(np.mean(fin2 <= ddl)),
+                         "serial_span_s": float(fin1.max()), "two_stage_span_s": float(fin2.max())}
+        counts = cb.calvo_pool_counts(srv.slots)
+        assert counts["used"] == 0 and not srv.flight, "slots left allocated after the trace"
+        return res, model
+    finally:
+        srv.close()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--requests", type=int, default=48)
     ap.add_argument("--load", type=float, default=1.2)
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--layers", type=int, default=8)
+    ap.add_argument("--two-stage", action="store_true",
+                    help="compare request-by-request service with loading and computation as two stages")
+    ap.add_argument("--max-query", type=int, default=MAX_QRY)
     args = ap.parse_args()
+    if args.two_stage:
+        res, _ = study_two_stage(args.requests, args.load, args.seed, args.layers, args.max_query)
+        print(f"{args.requests} requests at {args.load:g} x capacity, {args.layers} layers, queries up to {args.max_query} tokens")
+        print(f"{'policy':<8}{'serial TTFT ms':>16}{'two-stage ms':>14}{'met':>6}{'met':>6}{'serial span ms':>16}{'two-stage ms':>14}")
+        for name, _ in POLICIES:
+            r = res[name]
+            print(f"{name:<8}{r['serial_ttft_s'] * 1e3:>16.1f}{r['two_stage_ttft_s'] * 1e3:>14.1f}{r['serial_met'] * 100:>5.0f}%"
+                  f"{r['two_stage_met'] * 100:>5.0f}%{r['serial_span_s'] * 1e3:>16.1f}{r['two_stage_span_s'] * 1e3:>14.1f}")
+        return
     res, _ = study(args.requests, args.load, args.seed, args.layers)
     print(f"{args.requests} requests at {args.load:g} x capacity, {args.layers} layers")
     print(f"{'policy':<8}{'mean TTFT ms':>14}{'replayed ms':>13}{'deadlines met':>15}{'replayed':>10}")
