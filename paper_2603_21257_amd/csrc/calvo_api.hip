@@ -80,11 +80,16 @@ struct calvo_ctx {
   bool tab_ing_pending = false;
   // attention-side descriptor blob: [ReqDesc x n][WorkItem x m][tables]
   int32_t* d_att = nullptr;
-  int32_t* h_att = nullptr;
+  // its pinned shadows: an upload reads its shadow when the compute stream gets to it, so a batch that
+  // differs from the previous one takes the next shadow instead of waiting for that upload (several
+  // requests can be queued on the compute stream without the calling thread blocking)
+  static constexpr int kShadows = 4;
+  int32_t* h_att[kShadows] = {nullptr, nullptr, nullptr, nullptr};
   size_t att_cap = 0;     // in int32
-  size_t att_len = 0;     // valid int32 in the shadow == on device
-  hipEvent_t ev_att = nullptr;
-  bool att_pending = false;
+  size_t att_len = 0;     // valid int32 in shadow att_cur == on device
+  int att_cur = 0;
+  hipEvent_t ev_att[kShadows] = {nullptr, nullptr, nullptr, nullptr};
+  bool att_pending[kShadows] = {false, false, false, false};
   std::vector<hipEvent_t> ev_t0, ev_t1;
   std::vector<char> timed;
   std::vector<int32_t> last_variant, last_wgs;   // per layer: attention kernel chosen, workgroups launched
@@ -133,11 +138,11 @@ void destroy_partial(calvo_ctx* c) {
     if (p) (void)hipHostFree(p);
   for (auto e : c->ev_l2_free) if (e) (void)hipEventDestroy(e);
   if (c->ev_tab_ing) (void)hipEventDestroy(c->ev_tab_ing);
-  if (c->ev_att) (void)hipEventDestroy(c->ev_att);
+  for (auto e : c->ev_att) if (e) (void)hipEventDestroy(e);
   if (c->d_tab_ing) (void)hipFree(c->d_tab_ing);
   if (c->h_tab_ing) (void)hipHostFree(c->h_tab_ing);
   if (c->d_att) (void)hipFree(c->d_att);
-  if (c->h_att) (void)hipHostFree(c->h_att);
+  for (auto h : c->h_att) if (h) (void)hipHostFree(h);
   if (c->part_o) (void)hipFree(c->part_o);
   if (c->part_ml) (void)hipFree(c->part_ml);
   for (auto& s : c->s_copy) if (s) (void)hipStreamDestroy(s);
@@ -225,16 +230,27 @@ int ensure_ing_table(calvo_ctx* c, size_t n) {
 
 int ensure_att_blob(calvo_ctx* c, size_t n) {
   if (n <= c->att_cap) return CALVO_OK;
-  if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
+  for (int k = 0; k < calvo_ctx::kShadows; k++)
+    if (c->att_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_att[k])); c->att_pending[k] = false; }
   HIP_TRY(hipStreamSynchronize(c->s_compute));
   size_t cap = std::max<size_t>(n, 8192);
-  int32_t *d = nullptr, *h = nullptr;
+  int32_t* d = nullptr;
+  int32_t* h[calvo_ctx::kShadows] = {nullptr, nullptr, nullptr, nullptr};
   HIP_TRY(hipMalloc((void**)&d, cap * 4));
-  hipError_t e = hipHostMalloc((void**)&h, cap * 4, hipHostMallocDefault);
-  if (e != hipSuccess) { (void)hipFree(d); return fail_hip(e, "hipHostMalloc(descriptor shadow)"); }
+  for (int k = 0; k < calvo_ctx::kShadows; k++) {
+    hipError_t e = hipHostMalloc((void**)&h[k], cap * 4, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipFree(d);
+      for (int j = 0; j < k; j++) (void)hipHostFree(h[j]);
+      return fail_hip(e, "hipHostMalloc(descriptor shadow)");
+    }
+  }
   if (c->d_att) (void)hipFree(c->d_att);
-  if (c->h_att) (void)hipHostFree(c->h_att);
-  c->d_att = d; c->h_att = h; c->att_cap = cap; c->att_len = 0;
+  for (int k = 0; k < calvo_ctx::kShadows; k++) {
+    if (c->h_att[k]) (void)hipHostFree(c->h_att[k]);
+    c->h_att[k] = h[k];
+  }
+  c->d_att = d; c->att_cap = cap; c->att_len = 0; c->att_cur = 0;
   return CALVO_OK;
 }
 
@@ -522,7 +538,7 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
     CREATE_TRY(hipEventCreate(&c->ev_t1[l]));
   }
   CREATE_TRY(hipEventCreateWithFlags(&c->ev_tab_ing, hipEventDisableTiming));
-  CREATE_TRY(hipEventCreateWithFlags(&c->ev_att, hipEventDisableTiming));
+  for (auto& e : c->ev_att) CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
 #undef CREATE_TRY
   if (cfg->dtype == CALVO_BF16 && cfg->head_dim == 128) {
     const int prc = ensure_partials(c, kPartialSlots0);
@@ -1057,15 +1073,17 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
     rc = ensure_partials(c, items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant));
     if (rc != CALVO_OK) return rc;
   }
-  const bool same = c->att_len == blob.size() && memcmp(c->h_att, blob.data(), blob.size() * 4) == 0;
+  const bool same = c->att_len == blob.size() && memcmp(c->h_att[c->att_cur], blob.data(), blob.size() * 4) == 0;
   if (!same) {
-    if (c->att_pending) { HIP_TRY(hipEventSynchronize(c->ev_att)); c->att_pending = false; }
+    const int k = (c->att_cur + 1) % calvo_ctx::kShadows;      // the shadow whose upload is the oldest
+    if (c->att_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_att[k])); c->att_pending[k] = false; }
     c->att_len = 0;                       // the device copy is unknown until the transfer is queued
-    memcpy(c->h_att, blob.data(), blob.size() * 4);
-    HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att, blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+    memcpy(c->h_att[k], blob.data(), blob.size() * 4);
+    HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att[k], blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+    c->att_cur = k;
     c->att_len = blob.size();
-    HIP_TRY(hipEventRecord(c->ev_att, c->s_compute));
-    c->att_pending = true;
+    HIP_TRY(hipEventRecord(c->ev_att[k], c->s_compute));
+    c->att_pending[k] = true;
   }
 
   if (!chunked) {
