@@ -203,7 +203,11 @@ int calvo_l3_wait(calvo_ctx* ctx, calvo_l3_stats* stats);
  *   CALVO_EV_HOST_WAIT    block the calling thread until it has
  *   CALVO_EV_STREAM_WAIT  make `stream` (a hipStream_t; NULL = the compute stream) wait for
  *                         it on the device; the host does not block
- * A layer that was never ingested through this context counts as ready. */
+ * A layer that was never ingested through this context counts as ready.  The signal of a layer
+ * belongs to the most recent loading call that covered the layer: to serve several requests through
+ * one context, queue a request's calvo_prefill_attn calls (they capture the signal when they are
+ * made) before the next request's loading call - its loading then runs while the first request still
+ * computes - or the earlier request's attention waits for the later load as well. */
 int calvo_layer_event(calvo_ctx* ctx, int layer, int mode, void* stream);
 
 /* Compute stage for one layer (paper Section 2.1 prefill over a reused prefix; Section 3.1:
