@@ -106,16 +106,13 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   const int pq_min = P + wq0;
   const int pq_max = P + min(wq0 + 32, S) - 1;
   const int ctx_len = P + S;
-  const int n_keys = P + min(q_base + TQ, S);
   // This work item covers the sub-tiles [jb, je) of the tile's context; t and j below count from jb.
   const int jb = wi.sub_begin;
   const int n_sub = wi.sub_end - jb;                           // sub-tiles this workgroup visits
   const int n_pipe = max(0, min(wi.sub_end, (P + q_base + 1) / kSK) - jb);   // ... fully visible to all its rows
   const int last_blk = (ctx_len + kBlockTokens - 1) / kBlockTokens - 1;
-  // the block table is read-only for the whole launch: reading it through the constant address
+  // the block offsets are read-only for the whole launch: reading them through the constant address
   // space keeps the lookups on the scalar unit, outside the vmcnt accounting of the K/V requests
-  typedef const __attribute__((address_space(4))) int32_t* const_i32p;
-  const const_i32p table = (const_i32p)(uintptr_t)(p.tables + rd.table_off);
   typedef const __attribute__((address_space(4))) int64_t* const_i64p;
   const int n_blk_pad = last_blk + 1 + kTablePad + ((last_blk + 1) & 1);            // entries of the padded table
   // this wave's half of every sub-tile: block 2j + (wave >> 2); offsets of one parity are contiguous
@@ -304,7 +301,7 @@ __global__ void __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(120))) 
   auto prefetch = [&](auto ks, auto vs) {
     static_for<0, kPD>([&](auto idx) { pre[decltype(idx)::value] = load_opnd(idx, ks, vs); });
   };
-  auto step_steady = [&](auto t8, auto mf, int t) {
+  auto step_steady = [&](auto t8, auto mf, int /*t*/) {
     constexpr int T8 = decltype(t8)::value;
     constexpr bool MF = decltype(mf)::value != 0;
     constexpr int I = (T8 + 7) & 7;                  // position inside the unrolled iteration

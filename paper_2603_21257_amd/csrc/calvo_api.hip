@@ -1011,7 +1011,6 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   }
 
   const calvo_config& cf = c->cfg;
-  const int G = cf.n_q_heads / cf.n_kv_heads;
   const bool mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
   const int HW = attn_heads_per_wg(cf.n_q_heads, cf.n_kv_heads);
   int variant = 0;
