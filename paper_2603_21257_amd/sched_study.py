@@ -15,7 +15,6 @@ computation part covers attention only, which is all this path computes.
 from __future__ import annotations
 
 import argparse
-import math
 
 import numpy as np
 

@@ -4,7 +4,6 @@ started chunk by chunk on what has landed (paper Section 3.1, the per-block sign
 The result is defined by the same oracle as the whole-layer path: pool bytes bit exact, attention
 within the stated tolerance, element by element.
 """
-import numpy as np
 import pytest
 import torch
 

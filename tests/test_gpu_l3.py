@@ -3,7 +3,6 @@ must hold exactly the bytes the oracle's ingest puts there, attention over it mu
 oracle, and the hand-over / readiness signals must behave as the header says."""
 import time
 
-import numpy as np
 import pytest
 import torch
 
