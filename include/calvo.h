@@ -227,6 +227,23 @@ int calvo_layer_event(calvo_ctx* ctx, int layer, int mode, void* stream);
 int calvo_prefill_attn(calvo_ctx* ctx, int layer, const void* q, const void* k_suffix, const void* v_suffix,
                        void* out, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale);
 
+/* The same operation for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, result and errors are
+ * those of calvo_prefill_attn; the call itself allocates nothing (no hipMalloc / hipFree / pinned
+ * allocation).  What calvo_prefill_attn keeps in buffers it grows on demand - the request
+ * descriptors, work items and block tables the kernels read, and the partial results of tiles whose
+ * context is cut into pieces - lives in one array of fixed size inside the library's device image
+ * (35.5 MiB per GPU, held until the process ends; its address is looked up once per device by
+ * calvo_create).  Limits: 262144 descriptor words (about 80000 table entries over the batch) and
+ * 2048 partial-result slots (pieces x head groups x waves per workgroup); a batch beyond either gets
+ * CALVO_ENOMEM with nothing queued - use calvo_prefill_attn for it (long layers loaded in chunks are
+ * the usual case).  The array is shared by every call on the GPU, whatever the context: calls are
+ * ordered by the compute stream they are queued on, and calls that overlap on one GPU from different
+ * streams or contexts race.  Nothing in it needs to start at zero (every word a kernel reads was
+ * written by the same call). */
+int calvo_prefill_attn_noalloc(calvo_ctx* ctx, int layer, const void* q, const void* k_suffix, const void* v_suffix,
+                               void* out, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale);
+
 /* ---- Inter-request scheduling (paper Section 3.2; compared policies: Section 4.3).  Host code only.
  *
  * Cost model: "a binary linear function" fitted by offline profiling - loading latency linear in the

@@ -47,6 +47,45 @@ int fail_hip(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(e_, #expr);  \
   } while (0)
 
+// ---- device memory for calvo_prefill_attn_noalloc: what calvo_prefill_attn keeps in buffers it
+// allocates (the descriptor blob and the split-KV partial results) lives here in one file-scope
+// array instead.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends; host code only ever uses the address obtained per device from
+// hipGetSymbolAddress (the array's name is not a device address on the host side).
+constexpr size_t kStaticBlobInts = (size_t)262144;                  // 1 MiB of descriptors: about 80000 table entries
+constexpr size_t kStaticPartSlots = 2048;                           // (work item, head group, wave) slots
+constexpr size_t kStaticBlobBytes = kStaticBlobInts * 4;
+constexpr size_t kStaticPartOBytes = kStaticPartSlots * 32 * 128 * sizeof(float);   // 32 MiB
+constexpr size_t kStaticPartMlBytes = kStaticPartSlots * 32 * 2 * sizeof(float);    // 512 KiB
+constexpr size_t kScratchBytes = kStaticBlobBytes + kStaticPartOBytes + kStaticPartMlBytes;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of this device's copy of the array (looked up once per device, with that device current).
+int scratch_for_device(int dev, unsigned char** out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(CALVO_EINVAL, "device index %d not supported", dev);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != dev) return fail(CALVO_EINVAL, "device %d is not the current device (%d)", dev, cur);
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(CALVO_EHIP, "hipGetSymbolAddress returned NULL");
+    g_scratch_ptr[dev] = (unsigned char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CALVO_OK;
+}
+
 }  // namespace
 
 struct calvo_ctx {
@@ -105,6 +144,13 @@ struct calvo_ctx {
   float* part_ml = nullptr;
   size_t part_slots = 0;          // capacity in (work item, head group, wave) slots
   int device = 0;
+  // ---- calvo_prefill_attn_noalloc: this device's static array and pinned shadows of fixed size
+  // (made by calvo_create) for the descriptor uploads
+  unsigned char* d_static = nullptr;
+  int32_t* h_static[kShadows] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev_static[kShadows] = {nullptr, nullptr, nullptr, nullptr};
+  bool static_pending[kShadows] = {false, false, false, false};
+  int static_cur = 0;
   // ---- emulated L3 -> L2 stage: a loader thread, a ring of pinned buffers, and the hand-over
   // state it shares with the calling thread (layer_issued, l3_*: guarded by mu)
   std::mutex mu;
@@ -143,6 +189,8 @@ void destroy_partial(calvo_ctx* c) {
   if (c->h_tab_ing) (void)hipHostFree(c->h_tab_ing);
   if (c->d_att) (void)hipFree(c->d_att);
   for (auto h : c->h_att) if (h) (void)hipHostFree(h);
+  for (auto h : c->h_static) if (h) (void)hipHostFree(h);
+  for (auto e : c->ev_static) if (e) (void)hipEventDestroy(e);
   if (c->part_o) (void)hipFree(c->part_o);
   if (c->part_ml) (void)hipFree(c->part_ml);
   for (auto& s : c->s_copy) if (s) (void)hipStreamDestroy(s);
@@ -539,7 +587,13 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
   }
   CREATE_TRY(hipEventCreateWithFlags(&c->ev_tab_ing, hipEventDisableTiming));
   for (auto& e : c->ev_att) CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  for (auto& e : c->ev_static) CREATE_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  for (auto& h : c->h_static) CREATE_TRY(hipHostMalloc((void**)&h, kStaticBlobBytes, hipHostMallocDefault));
 #undef CREATE_TRY
+  {
+    const int src = scratch_for_device(dev, &c->d_static);
+    if (src != CALVO_OK) { destroy_partial(c); return src; }
+  }
   if (cfg->dtype == CALVO_BF16 && cfg->head_dim == 128) {
     const int prc = ensure_partials(c, kPartialSlots0);
     if (prc != CALVO_OK) { destroy_partial(c); return prc; }
@@ -982,8 +1036,10 @@ int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
   return CALVO_OK;
 }
 
-int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
-                       const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
+// use_static: descriptors and split-KV partial results go to this device's file-scope array and
+// nothing is allocated (calvo_prefill_attn_noalloc); otherwise to buffers the context grows on demand.
+static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
+                             const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale, bool use_static) {
   if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
   std::vector<char> seen;
@@ -1066,13 +1122,40 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   const size_t items_off = lay.items_off, split_off = lay.split_off, tables_off = lay.tables_off, offs_off = lay.offs_off;
   const std::vector<size_t>& group_off = lay.group_off;
 
-  rc = ensure_att_blob(c, blob.size());
-  if (rc != CALVO_OK) return rc;
-  if (!split_tiles.empty()) {
-    rc = ensure_partials(c, items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant));
+  const size_t part_need = split_tiles.empty() ? 0 : items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant);
+  int32_t* d_att = c->d_att;
+  float *part_o = c->part_o, *part_ml = c->part_ml;
+  if (use_static) {
+    // fixed capacity, no allocation: the array is shared by every call on this GPU, so its
+    // descriptors are uploaded on every call (another context may have used it in between)
+    if (blob.size() > kStaticBlobInts)
+      return fail(CALVO_ENOMEM, "calvo_prefill_attn_noalloc: the batch needs %zu descriptor words, the static array holds %zu "
+                  "(use calvo_prefill_attn)", blob.size(), kStaticBlobInts);
+    if (part_need > kStaticPartSlots)
+      return fail(CALVO_ENOMEM, "calvo_prefill_attn_noalloc: the launch needs %zu partial-result slots, the static array holds %zu "
+                  "(use calvo_prefill_attn)", part_need, kStaticPartSlots);
+    d_att = (int32_t*)c->d_static;
+    part_o = (float*)(c->d_static + kStaticBlobBytes);
+    part_ml = (float*)(c->d_static + kStaticBlobBytes + kStaticPartOBytes);
+    const int k = (c->static_cur + 1) % calvo_ctx::kShadows;
+    if (c->static_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_static[k])); c->static_pending[k] = false; }
+    memcpy(c->h_static[k], blob.data(), blob.size() * 4);
+    HIP_TRY(hipMemcpyAsync(d_att, c->h_static[k], blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+    HIP_TRY(hipEventRecord(c->ev_static[k], c->s_compute));
+    c->static_pending[k] = true;
+    c->static_cur = k;
+  } else {
+    rc = ensure_att_blob(c, blob.size());
     if (rc != CALVO_OK) return rc;
+    if (part_need) {
+      rc = ensure_partials(c, part_need);
+      if (rc != CALVO_OK) return rc;
+    }
+    d_att = c->d_att;
+    part_o = c->part_o;
+    part_ml = c->part_ml;
   }
-  const bool same = c->att_len == blob.size() && memcmp(c->h_att[c->att_cur], blob.data(), blob.size() * 4) == 0;
+  const bool same = use_static || (c->att_len == blob.size() && memcmp(c->h_att[c->att_cur], blob.data(), blob.size() * 4) == 0);
   if (!same) {
     const int k = (c->att_cur + 1) % calvo_ctx::kShadows;      // the shadow whose upload is the oldest
     if (c->att_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_att[k])); c->att_pending[k] = false; }
@@ -1094,8 +1177,8 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   if (!chunked && layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
 
   unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
-  const ReqDesc* d_reqs = (const ReqDesc*)c->d_att;
-  const int32_t* d_tables = c->d_att + tables_off;
+  const ReqDesc* d_reqs = (const ReqDesc*)d_att;
+  const int32_t* d_tables = d_att + tables_off;
 
   if (k_suffix) {
     AppendParams ap{};
@@ -1107,16 +1190,16 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
 
   AttnParams p{};
   p.q = q; p.out = out; p.pool_layer = pool_layer;
-  p.reqs = d_reqs; p.items = (const WorkItem*)(c->d_att + items_off); p.tables = d_tables;
-  p.blk_offs = (const int64_t*)(c->d_att + offs_off);
+  p.reqs = d_reqs; p.items = (const WorkItem*)(d_att + items_off); p.tables = d_tables;
+  p.blk_offs = (const int64_t*)(d_att + offs_off);
   p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
   p.heads_per_wg = HW; p.tile_tokens = tile_tokens;
   p.waves_per_wg = attn_mfma_waves_per_wg(variant);
   p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
   HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
   if (mfma) {
-    p.part_o = c->part_o;
-    p.part_ml = c->part_ml;
+    p.part_o = part_o;
+    p.part_ml = part_ml;
     if (chunked) {
       for (size_t g = 0; g < groups.size(); g++) {
         // a device-side wait needs a recorded event: with a loader running, this thread follows it chunk by chunk
@@ -1129,7 +1212,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
         }
         if (groups[g].empty()) continue;
         p.n_items = (int32_t)groups[g].size();
-        p.item_index = c->d_att + group_off[g];
+        p.item_index = d_att + group_off[g];
         HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
       }
       p.item_index = nullptr;
@@ -1137,7 +1220,7 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
       p.n_items = (int32_t)items.size();
       HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
     }
-    HIP_TRY(launch_merge_splits(p, c->d_att + split_off, (int)split_tiles.size(), c->s_compute));
+    HIP_TRY(launch_merge_splits(p, d_att + split_off, (int)split_tiles.size(), c->s_compute));
   } else {
     p.n_items = n_reqs;
     HIP_TRY(launch_attn_simple(p, cf.dtype, total, c->s_compute));
@@ -1147,6 +1230,16 @@ int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suf
   c->last_variant[layer] = mfma ? variant : -1;
   c->last_wgs[layer] = mfma ? (int32_t)(items.size() * (size_t)(cf.n_q_heads / HW)) : 0;
   return CALVO_OK;
+}
+
+int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
+                       const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
+  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, false);
+}
+
+int calvo_prefill_attn_noalloc(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
+                               const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
+  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, true);
 }
 
 int calvo_attn_kernel_info(calvo_ctx* c, int layer, int* kernel, int* n_workgroups) {

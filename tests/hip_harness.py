@@ -56,10 +56,12 @@ def make_requests(w: wl.Workload, host: torch.Tensor):
 
 
 def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_streams: int = 0,
-            scale: float = 0.0, append_suffix: bool = True, chunk_blocks=None):
+            scale: float = 0.0, append_suffix: bool = True, chunk_blocks=None, attn_fn=None):
     """Whole path on cuda:0.  Returns (pool image as stored-dtype numpy [L][slots][elems],
     out as stored-dtype numpy [L][T][Hq][D]).  chunk_blocks: per-layer chunk sizes for the
-    chunk-granular load (None: whole layers)."""
+    chunk-granular load (None: whole layers).  attn_fn: the binding function that runs the
+    attention stage (default calvo_prefill_attn)."""
+    attn_fn = attn_fn or cb.calvo_prefill_attn
     s = w.shape
     dev = torch.device("cuda:0")
     dt = torch_dtype(s)
@@ -81,9 +83,9 @@ def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_s
         else:
             cb.calvo_kv_ingest_chunked(ctx, reqs, 0, s.n_layers, chunk_blocks)
         for l in range(s.n_layers):
-            cb.calvo_prefill_attn(ctx, l, q[l] if T else None, (ks[l] if append_suffix and T else None),
-                                  (vs[l] if append_suffix and T else None), out[l] if T else None,
-                                  reqs, w.cu_suffix, scale)
+            attn_fn(ctx, l, q[l] if T else None, (ks[l] if append_suffix and T else None),
+                    (vs[l] if append_suffix and T else None), out[l] if T else None,
+                    reqs, w.cu_suffix, scale)
         for l in range(s.n_layers):
             assert cb.calvo_layer_event(ctx, l, cb.CALVO_EV_HOST_WAIT)
     finally:
