@@ -20,7 +20,8 @@ CALVO_OK, CALVO_EINVAL, CALVO_ENOMEM, CALVO_EHIP, CALVO_ENOTREADY = 0, -1, -2, -
 CALVO_BF16, CALVO_F32 = 0, 1
 CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
+# CALVO_LIB names another build of the library (A/B timing of two builds); default: the in-tree one
+LIB_PATH = os.environ.get("CALVO_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
            "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_prefill_attn_noalloc", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcalvo.so")
-SOURCES = ["calvo_api.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_mfma.hip", "attn_pipe.hip", "attn_duo.hip", "attn_plan.cpp", "ingest_plan.cpp", "calvo_sched.cpp", "calvo_pool.cpp"]
+SOURCES = ["calvo_api.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_pipe.hip", "attn_duo.hip", "attn_plan.cpp", "ingest_plan.cpp", "calvo_sched.cpp", "calvo_pool.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-fno-gpu-rdc"]
@@ -27,25 +27,6 @@ def build(verbose: bool = False) -> str:
     if verbose and out.strip():
         print(out)
     return LIB
-
-
-PROBES = ["probe_coissue.hip", "probe_valu_issue.hip"]      # stand-alone microbenchmarks, not part of the library
-
-
-def build_probes(outdir: str) -> list:
-    """Compiles the microbenchmarks into outdir (they are run by hand on a GPU machine)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    os.makedirs(outdir, exist_ok=True)
-    made = []
-    for src in PROBES:
-        exe = os.path.join(outdir, os.path.splitext(src)[0])
-        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", os.path.join(CSRC, src), "-o", exe]
-        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        if res.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n" + res.stdout)
-        made.append(exe)
-    return made
 
 
 if __name__ == "__main__":

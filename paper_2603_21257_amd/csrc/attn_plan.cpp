@@ -8,11 +8,39 @@
 #include "attn_plan.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <functional>
 
 #include "../../include/calvo.h"
 
 namespace calvo {
+
+int attn_pipe_tile_tokens(int heads_per_wg);
+int attn_duo_tile_tokens(int heads_per_wg);
+
+// Two shapes of the pipelined kernel serve bf16 / head-dim-128 batches: kAttnPipe (8-wave workgroups,
+// 64-token tiles for four heads: half the K/V traffic into LDS per query row) and kAttnDuo (two
+// 4-wave workgroups per CU, 32-token tiles).  With the short queries of the paper's Table 1 half of
+// a 64-token tile's waves would idle, so the smaller tiles win there.  The environment variable
+// CALVO_ATTN_VARIANT (3 or 4, read per call: tests switch it inside one process) forces one.
+int attn_mfma_choose(const int32_t* suffix_lens, int n_reqs, int heads_per_wg) {
+  const char* e = getenv("CALVO_ATTN_VARIANT");
+  if (e && (e[0] == '3' || e[0] == '4') && e[1] == 0) return e[0] - '0';
+  // query rows the tiles of each kernel would hold, empty ones included
+  const int t3 = attn_pipe_tile_tokens(heads_per_wg), t4 = attn_duo_tile_tokens(heads_per_wg);
+  int64_t rows3 = 0, rows4 = 0;
+  for (int r = 0; r < n_reqs; r++) {
+    rows3 += (int64_t)((suffix_lens[r] + t3 - 1) / t3) * t3;
+    rows4 += (int64_t)((suffix_lens[r] + t4 - 1) / t4) * t4;
+  }
+  return rows3 * 9 > rows4 * 10 ? kAttnDuo : kAttnPipe;       // the larger tiles would carry over 10 % more rows
+}
+
+int attn_mfma_waves_per_wg(int variant) { return variant == kAttnPipe ? 8 : 4; }
+
+int attn_mfma_tile_tokens(int variant, int heads_per_wg) {
+  return variant == kAttnDuo ? attn_duo_tile_tokens(heads_per_wg) : attn_pipe_tile_tokens(heads_per_wg);
+}
 
 std::vector<PlanTile> plan_tiles(const int32_t* prefix_blocks, const int32_t* suffix_lens, int n_reqs, int tile_tokens) {
   std::vector<PlanTile> tiles;
@@ -128,10 +156,10 @@ extern "C" int calvo_attn_plan_items(int32_t n_q_heads, int32_t n_kv_heads, int3
   const std::vector<PlanTile> tiles = plan_tiles(prefix_blocks, suffix_lens, n_reqs, attn_mfma_tile_tokens(variant, hw));
   const PlanParams p{n_q_heads / hw, n_cus * (8 / attn_mfma_waves_per_wg(variant)), 48, 30, 0};
   PlanItems pi;
-  if (chunk_blocks > 0 && attn_mfma_splits_context(variant)) {
+  if (chunk_blocks > 0) {
     pi = plan_items_chunked(tiles, prefix_blocks, chunk_blocks, (max_blocks + chunk_blocks - 1) / chunk_blocks);
   } else {
-    pi = plan_items(tiles, attn_mfma_splits_context(variant) ? plan_pieces(tiles, p) : 1, p);
+    pi = plan_items(tiles, plan_pieces(tiles, p), p);
   }
   *n_items = (int32_t)pi.items.size();
   if ((int64_t)pi.items.size() > capacity) return CALVO_ENOMEM;
@@ -159,7 +187,7 @@ extern "C" int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_
   const int tt = attn_mfma_tile_tokens(variant, hw);
   const std::vector<PlanTile> tiles = plan_tiles(prefix_blocks, suffix_lens, n_reqs, tt);
   PlanParams p{n_q_heads / hw, n_cus * (8 / attn_mfma_waves_per_wg(variant)), 48, 30, 0};
-  const int want = attn_mfma_splits_context(variant) ? plan_pieces(tiles, p) : 1;
+  const int want = plan_pieces(tiles, p);
   int64_t items = 0;
   for (const PlanTile& t : tiles) {
     const int len = plan_piece_len(t.n_sub, want, p);

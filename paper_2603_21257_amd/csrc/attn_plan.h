@@ -6,10 +6,12 @@
 
 namespace calvo {
 
-// which MFMA kernel serves a batch with these suffix lengths (see attn_mfma.hip); the other calls take its answer
+// which shape of the pipelined MFMA kernel serves a batch with these suffix lengths (attn_plan.cpp);
+// the other calls take its answer
+constexpr int kAttnPipe = 3;   // 8-wave workgroups, 64-token tiles
+constexpr int kAttnDuo = 4;    // two 4-wave workgroups per CU, 32-token tiles
 int attn_mfma_choose(const int32_t* suffix_lens, int n_reqs, int heads_per_wg);
 int attn_mfma_tile_tokens(int variant, int heads_per_wg);
-bool attn_mfma_splits_context(int variant);   // whether that kernel handles work items with n_splits > 1
 int attn_mfma_waves_per_wg(int variant);
 
 // query heads of one KV group that share a workgroup: 4, 2 or 1 (the largest that divides the group)

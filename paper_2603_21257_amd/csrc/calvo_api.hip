@@ -595,6 +595,12 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
     if (src != CALVO_OK) { destroy_partial(c); return src; }
   }
   if (cfg->dtype == CALVO_BF16 && cfg->head_dim == 128) {
+    // the pipelined kernels use more dynamic LDS than the default limit (a per-device attribute)
+    hipError_t e = attn_pipe_prepare();
+    if (e == hipSuccess) e = attn_duo_prepare();
+    if (e != hipSuccess) { const int prc = fail_hip(e, "hipFuncSetAttribute(dynamic LDS)"); destroy_partial(c); return prc; }
+  }
+  if (cfg->dtype == CALVO_BF16 && cfg->head_dim == 128) {
     const int prc = ensure_partials(c, kPartialSlots0);
     if (prc != CALVO_OK) { destroy_partial(c); return prc; }
   }
@@ -1036,6 +1042,10 @@ int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
   return CALVO_OK;
 }
 
+static hipError_t launch_attn(int variant, const AttnParams& p, hipStream_t stream) {
+  return variant == kAttnDuo ? launch_attn_duo(p, stream) : launch_attn_pipe(p, stream);
+}
+
 // use_static: descriptors and split-KV partial results go to this device's file-scope array and
 // nothing is allocated (calvo_prefill_attn_noalloc); otherwise to buffers the context grows on demand.
 static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
@@ -1087,7 +1097,7 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
     nck = c->n_chunks[layer];
   }
   // a layer loaded in chunks: attention follows the chunks, one launch behind each chunk's event
-  const bool chunked = mfma && cb > 0 && attn_mfma_splits_context(variant) && !c->force_splits;
+  const bool chunked = mfma && cb > 0 && !c->force_splits;
   if (mfma) {
     std::vector<int32_t> pblocks(n_reqs), slens(n_reqs);
     for (int r = 0; r < n_reqs; r++) { pblocks[r] = reqs[r].n_prefix_blocks; slens[r] = reqs[r].suffix_len; }
@@ -1098,7 +1108,7 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
       plan = plan_items_chunked(tiles, pblocks.data(), cb, nck);
     } else {
       int want = 1;
-      if (attn_mfma_splits_context(variant)) {
+      {
         // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
         // is kept for the following layers
         std::vector<int64_t> key;
@@ -1213,12 +1223,12 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
         if (groups[g].empty()) continue;
         p.n_items = (int32_t)groups[g].size();
         p.item_index = d_att + group_off[g];
-        HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
+        HIP_TRY(launch_attn(variant, p, c->s_compute));
       }
       p.item_index = nullptr;
     } else {
       p.n_items = (int32_t)items.size();
-      HIP_TRY(launch_attn_mfma(variant, p, c->s_compute));
+      HIP_TRY(launch_attn(variant, p, c->s_compute));
     }
     HIP_TRY(launch_merge_splits(p, d_att + split_off, (int)split_tiles.size(), c->s_compute));
   } else {

@@ -34,10 +34,9 @@ struct AttnParams {
   float scale;              // softmax scale (natural-exponent units)
   // split-KV partial results, used by work items with n_splits > 1: per work item, head group, wave
   // (head of the group x 32-token half of the tile): part_o [32 rows][D] fp32 unnormalised,
-  // part_ml [32 rows][2] = (running maximum in score units, row sum)
+  // part_ml [32 rows][2] = (softmax reference in exponent units, i.e. score * scale * log2 e, row sum)
   float* part_o;
   float* part_ml;
-  long long* prof;          // phase-timing builds only (CALVO_PHASE_PROF): one counter per wave, else NULL
 };
 
 struct AppendParams {
@@ -56,7 +55,10 @@ hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_
                                  int32_t blk_bytes, int grid, hipStream_t stream);
 hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
-hipError_t launch_attn_mfma(int variant, const AttnParams& p, hipStream_t stream);
+// The pipelined bf16 / head-dim-128 kernels (attn_pipeline.h).  The *_prepare calls raise the
+// kernels' dynamic LDS limit; once per device, before the first launch.
+hipError_t attn_pipe_prepare();
+hipError_t attn_duo_prepare();
 hipError_t launch_attn_pipe(const AttnParams& p, hipStream_t stream);
 hipError_t launch_attn_duo(const AttnParams& p, hipStream_t stream);
 int attn_duo_tile_tokens(int heads_per_wg);
