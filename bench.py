@@ -50,7 +50,6 @@ def main():
     ap.add_argument("--mode", choices=["full", "attn", "ingest"], default="full",
                     help="attn / ingest: run only that stage `steps` times (for profiling); no JSON contract line")
     ap.add_argument("--n-staging", type=int, default=0)
-    ap.add_argument("--copy-streams", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--custom", type=str, default="",
                     help="replace the workload's requests by 'P:S[,P:S...]' (prefix:suffix tokens) on the same model shape, "
@@ -127,8 +126,7 @@ def main():
                             r.n_prefix_blocks, r.suffix_len, r.first_ingest_block) for r in w.requests]
     ctx = cb.calvo_create(L, s.n_q_heads, s.n_kv_heads, s.head_dim,
                           cb.CALVO_BF16 if s.dtype == "bf16" else cb.CALVO_F32, s.pool_blocks, pool,
-                          staging_bytes=args.staging_mib << 20, n_staging=args.n_staging,
-                          n_copy_streams=args.copy_streams)
+                          staging_bytes=args.staging_mib << 20, n_staging=args.n_staging)
 
     def poison():
         pool.view(torch.int16 if tdt == torch.bfloat16 else torch.int32).fill_(0x7FC1 if tdt == torch.bfloat16 else 0x7FC12345)

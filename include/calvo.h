@@ -42,8 +42,15 @@
  * workgroups of the zero-copy scatter; CALVO_MERGE_MIB = most bytes of
  * consecutive small layers that one transfer carries (default 256, 0 = every
  * layer by itself).  Read by every calvo_prefill_attn:
- * CALVO_ATTN_VARIANT = 3 or 4 forces the 8-wave or the 4-wave bf16 kernel
- * (other values 0-2: the unpipelined comparison kernels).
+ * CALVO_ATTN_VARIANT = 3 or 4 forces the 8-wave or the 4-wave bf16 kernel.
+ * Test hooks, read by calvo_create: CALVO_INGEST_DELAY_US = n makes the host
+ * sleep n microseconds before it queues each transfer of the L2 -> L1 stage
+ * (the loading stage becomes the slow one; nothing on the device changes);
+ * CALVO_TEST_SCATTER_DELAY_US = n puts a bounded delay kernel of n microseconds
+ * in front of every staged scatter (the scatter becomes the slow stage, so the
+ * reuse of the staging ring is exercised against its worst timing);
+ * CALVO_TEST_L3_FAIL_CHUNK = k makes the L3 loader report a failure instead of
+ * moving its chunk number k (error handling can then be tested without a fault).
  */
 #ifndef CALVO_H
 #define CALVO_H
@@ -74,7 +81,9 @@ typedef struct {
                             0 selects the zero-copy ingest: the scatter kernel reads the pinned
                             host blocks directly over PCIe and no staging buffer is allocated */
   int32_t n_staging;     /* number of staging buffers in the ring, 2..8 (0 = 2) */
-  int32_t n_copy_streams;/* 1 or 2 streams issuing the host-to-device copies (0 = 1) */
+  int32_t n_copy_streams;/* 0 or 1: one stream issues the host-to-device copies (one copy-engine stream
+                            already fills the link; a second one has to share a hardware queue with the
+                            compute stream and serialises loading with attention) */
   void*   compute_stream;/* hipStream_t the attention work is queued on, caller-owned;
                             NULL = the library creates and owns one */
 } calvo_config;
@@ -122,9 +131,8 @@ int calvo_destroy(calvo_ctx* ctx);
  * blocks; CALVO_EHIP if HIP refuses a transfer (queued work so far still completes). */
 int calvo_kv_ingest(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end);
 
-/* Chunk-granular readiness (paper Section 3.1: "each time a stage completes loading a KVCache
- * block, it would issue a signal to the upper-level stage" so that the stage above can start on what
- * has landed).  Same loads and same final pool bytes as calvo_kv_ingest; in addition layer l (entry
+/* Chunk-granular readiness (paper Section 3.1: a stage signals the stage above for every block it
+ * has finished loading, so that the stage above can start on what has landed).  Same loads and same final pool bytes as calvo_kv_ingest; in addition layer l (entry
  * l - layer_begin of chunk_blocks, HOST array of layer_end - layer_begin entries) is loaded in chunks
  * of chunk_blocks block indices: chunk k = blocks [k*cb, (k+1)*cb) of every request's table, chunks in
  * ascending order, one event per chunk recorded after its last store.  When chunk k's event has fired,
@@ -181,7 +189,10 @@ typedef struct {
 /* Same result in the pool as calvo_kv_ingest (raw bytes, bit exact, nothing else written), with the
  * source in pageable host memory and the L3 -> L2 stage described above in front.  Returns after
  * validation and after starting the loader thread; loading proceeds in the background.  The source
- * memory must stay valid and unchanged until calvo_l3_wait (or the last layer's event).  While a
+ * memory must stay valid and unchanged until calvo_l3_wait (or the last layer's event).  A failure
+ * inside the loader is returned once, by the first later call that depends on it (calvo_l3_wait, a
+ * loading call, calvo_layer_event / calvo_prefill_attn on a layer it did not hand over); that call
+ * also un-marks those layers, and the context can load again.  While a
  * loader runs, calvo_layer_event(QUERY) reports CALVO_ENOTREADY for layers not yet handed over,
  * HOST_WAIT / STREAM_WAIT and calvo_prefill_attn block the calling thread until the layer's last
  * chunk has been handed to the L2 -> L1 stage (the wait for L1 residency itself stays on the
@@ -246,7 +257,7 @@ int calvo_prefill_attn_noalloc(calvo_ctx* ctx, int layer, const void* q, const v
 
 /* ---- Inter-request scheduling (paper Section 3.2; compared policies: Section 4.3).  Host code only.
  *
- * Cost model: "a binary linear function" fitted by offline profiling - loading latency linear in the
+ * Cost model: a linear function of two variables fitted by offline profiling - loading latency linear in the
  * number of context tokens to load, computation latency linear in the number of query tokens:
  *     T_load = load_per_token_s * ctx_tokens + load_fixed_s      (0 when ctx_tokens == 0)
  *     T_comp = comp_per_token_s * query_tokens + comp_fixed_s    (0 when query_tokens == 0)
@@ -290,7 +301,7 @@ int calvo_sched_pick(int policy, const calvo_cost_model* model, const calvo_job*
  * load then compute.  pipelined == 1: loading and computation are separate stages (Section 3.1), a
  * job is taken when the loading stage is free and computes when its load has finished and the compute
  * stage is free, in loading order.  pipelined == 2: both stages serve their highest-priority ready
- * request ("the highest-priority request" of Section 3.1, per stage): the loading stage picks among
+ * request (Section 3.1: every stage dispatches by priority): the loading stage picks among
  * the arrived jobs, the compute stage among the loaded ones, decisions in time order, the compute stage
  * first at equal times.  Whenever the (loading) stage is free and a job has arrived, the policy picks; if
  * none has arrived the server idles until the next arrival.  Outputs: start_s[i] (loading starts) and
@@ -300,8 +311,8 @@ int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_
 
 /* ---- Slot allocation for the paged KV space with proactive reservation (paper Section 3.1:
  * when a lower-level transfer is issued, the destination space one level up is requested at the same
- * time, so a block can move on as soon as it arrives; footnote: if HBM is short this "simply degrades
- * to the reactive allocation").  Host code only; thread safe.  A slot carries a reference count: a
+ * time, so a block can move on as soon as it arrives; its footnote: when HBM is short the scheme
+ * falls back to allocating reactively, when space comes back).  Host code only; thread safe.  A slot carries a reference count: a
  * prefix run shared by several requests is referenced once per request and becomes free when the
  * last one releases it.  Which free slot a call hands out is unspecified (distinct, in range, free). */
 typedef struct calvo_pool calvo_pool;
@@ -390,6 +401,16 @@ int calvo_attn_plan_items(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, 
  * how many workgroups its work items made (*n_workgroups; 0 for the vector-ALU kernel).  Either
  * output may be NULL.  CALVO_ENOTREADY if none was queued. */
 int calvo_attn_kernel_info(calvo_ctx* ctx, int layer, int* kernel, int* n_workgroups);
+
+/* Measurement helper: the rate the matrix pipes of the current device sustain on bf16 MFMAs alone
+ * (v_mfma_f32_32x32x16_bf16, two waves per SIMD on every CU, operands in registers), for the operand
+ * data the caller supplies: operands = DEVICE, 16 KiB of bf16 values (the first 8 KiB feed the A
+ * operands, the rest the B operands); sink = DEVICE, at least 512 * 4 bytes per compute unit, receives
+ * the accumulators.  Runs on the default stream: one warm-up launch, then `repeats` launches of `iters`
+ * x 16 MFMAs per wave; *tflops = the fastest of them, *ms (may be NULL) its duration.  The published
+ * peak assumes the top clock; the sustained rate depends on how much the operand bits toggle.
+ * CALVO_EINVAL for bad arguments, CALVO_EHIP if HIP refuses. */
+int calvo_mfma_peak(const void* operands, void* sink, int iters, int repeats, double* tflops, double* ms);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* calvo_last_error(void);

@@ -23,7 +23,7 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 # CALVO_LIB names another build of the library (A/B timing of two builds); default: the in-tree one
 LIB_PATH = os.environ.get("CALVO_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_prefill_attn_noalloc", "calvo_attn_kernel_ms", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_prefill_attn_noalloc", "calvo_attn_kernel_ms", "calvo_mfma_peak", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
            "calvo_pool_cancel", "calvo_last_error"]
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
         L.calvo_prefill_attn_noalloc.argtypes = L.calvo_prefill_attn.argtypes
+        L.calvo_mfma_peak.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
         L.calvo_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -239,6 +240,13 @@ def calvo_prefill_attn_noalloc(ctx: int, layer: int, q, k_suffix, v_suffix, out,
     _check(lib().calvo_prefill_attn_noalloc(ctx, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out),
                                             _req_array(reqs), len(reqs), cu.ctypes.data_as(C.POINTER(C.c_int32)),
                                             float(scale)))
+
+
+def calvo_mfma_peak(operands, sink, iters: int = 20000, repeats: int = 3):
+    """(TFLOP/s, ms) the matrix pipes sustain on bf16 MFMAs alone with the given operand data (device buffers)."""
+    tf, ms = C.c_double(), C.c_double()
+    _check(lib().calvo_mfma_peak(_ptr(operands), _ptr(sink), int(iters), int(repeats), C.byref(tf), C.byref(ms)))
+    return tf.value, ms.value
 
 
 def _darr(x):

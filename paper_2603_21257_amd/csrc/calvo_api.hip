@@ -94,7 +94,7 @@ struct calvo_ctx {
   int64_t layer_bytes = 0;
   int n_staging = 0, n_copy = 0;
   int64_t staging_blocks = 0;
-  hipStream_t s_copy[2] = {nullptr, nullptr};
+  hipStream_t s_copy[1] = {nullptr};
   hipStream_t s_scatter = nullptr;
   hipStream_t s_compute = nullptr;
   bool own_compute = false;
@@ -144,6 +144,12 @@ struct calvo_ctx {
   float* part_ml = nullptr;
   size_t part_slots = 0;          // capacity in (work item, head group, wave) slots
   int device = 0;
+  // test hooks (environment, read by calvo_create): the host sleeps this long before it queues each
+  // transfer of the L2 -> L1 stage (makes the loading stage the slow one without touching the
+  // device); the L3 loader reports a failure instead of moving chunk number test_l3_fail_chunk
+  int test_ingest_delay_us = 0;
+  int test_scatter_delay_us = 0;     // a delay kernel in front of every scatter: the scatter becomes the slow stage
+  int test_l3_fail_chunk = -1;
   // ---- calvo_prefill_attn_noalloc: this device's static array and pinned shadows of fixed size
   // (made by calvo_create) for the descriptor uploads
   unsigned char* d_static = nullptr;
@@ -215,7 +221,7 @@ int validate_config(const calvo_config* cfg) {
   if (((uintptr_t)cfg->pool & 15) != 0) return fail(CALVO_EINVAL, "pool must be 16-byte aligned");
   if (cfg->n_staging != 0 && (cfg->n_staging < 2 || cfg->n_staging > 8))
     return fail(CALVO_EINVAL, "n_staging must be 0 or in [2, 8]");
-  if (cfg->n_copy_streams < 0 || cfg->n_copy_streams > 2) return fail(CALVO_EINVAL, "n_copy_streams must be 0, 1 or 2");
+  if (cfg->n_copy_streams < 0 || cfg->n_copy_streams > 1) return fail(CALVO_EINVAL, "n_copy_streams must be 0 or 1");
   const size_t elt = cfg->dtype == CALVO_BF16 ? 2 : 4;
   const size_t blk = (size_t)2 * kBlockTokens * cfg->n_kv_heads * cfg->head_dim * elt;
   if (cfg->staging_bytes != 0 && cfg->staging_bytes < blk)
@@ -323,36 +329,53 @@ int ensure_partials(calvo_ctx* c, size_t slots) {
   return CALVO_OK;
 }
 
-// Waits for a running L3 loader and returns its status (CALVO_OK if none ran).
+// Waits for a running L3 loader and returns its status (CALVO_OK if none ran).  A failure is
+// reported once: the call that returns it also forgets it and un-marks the layers the loader did
+// not hand over, so that the context can load again.
 int join_loader(calvo_ctx* c) {
   if (c->loader_started) {
     if (c->loader.joinable()) c->loader.join();
     c->loader_started = false;
   }
   std::lock_guard<std::mutex> lk(c->mu);
-  if (c->l3_status != CALVO_OK) g_err = c->l3_err;
-  return c->l3_status;
+  const int rc = c->l3_status;
+  if (rc != CALVO_OK) {
+    g_err = c->l3_err;
+    c->l3_status = CALVO_OK;
+    c->l3_err.clear();
+    for (size_t l = 0; l < c->layer_pending.size(); l++)
+      if (c->layer_pending[l]) {
+        c->layer_pending[l] = 0;
+        c->layer_issued[l] = 0;
+        c->chunks_issued[l] = 0;
+        c->n_chunks[l] = 0;
+        c->chunk_blocks[l] = 0;
+      }
+  }
+  return rc;
 }
 
-// Blocks until a running loader has handed `layer` to the L2->L1 stage (or failed).
+// Blocks until a running loader has handed `layer` to the L2->L1 stage (or failed; the failure is
+// then reported here and forgotten, see join_loader).
 int wait_handed_over(calvo_ctx* c, int layer) {
-  std::unique_lock<std::mutex> lk(c->mu);
-  c->cv.wait(lk, [&] { return !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
-  if (c->layer_pending[layer]) {
-    g_err = c->l3_err;
-    return c->l3_status;
+  {
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv.wait(lk, [&] { return !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
+    if (!c->layer_pending[layer]) return CALVO_OK;
   }
-  return CALVO_OK;
+  return join_loader(c);        // the loader has failed: it is about to exit
 }
 
 // Blocks until chunk `chunk` of `layer` has been handed to the L2->L1 stage, i.e. its event has been
 // recorded (at once unless a loader is still running), or the loader failed.
 int wait_chunk_handed_over(calvo_ctx* c, int layer, int chunk) {
-  std::unique_lock<std::mutex> lk(c->mu);
-  c->cv.wait(lk, [&] { return c->chunks_issued[layer] > chunk || !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
-  if (c->chunks_issued[layer] > chunk) return CALVO_OK;
-  g_err = c->l3_err;
-  return c->l3_status != CALVO_OK ? c->l3_status : CALVO_ENOTREADY;
+  {
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv.wait(lk, [&] { return c->chunks_issued[layer] > chunk || !c->layer_pending[layer] || c->l3_status != CALVO_OK; });
+    if (c->chunks_issued[layer] > chunk) return CALVO_OK;
+    if (c->l3_status == CALVO_OK) return fail(CALVO_ENOTREADY, "chunk %d of layer %d was not loaded", chunk, layer);
+  }
+  return join_loader(c);
 }
 
 bool layer_is_issued(calvo_ctx* c, int layer) {
@@ -369,11 +392,13 @@ hipError_t enqueue_staged(calvo_ctx* c, const unsigned char* pinned_src, unsigne
   const int b = (int)(c->seq % (uint64_t)c->n_staging);
   hipStream_t cs = c->s_copy[c->seq % (uint64_t)c->n_copy];
   hipError_t e;
+  if (c->test_ingest_delay_us > 0) std::this_thread::sleep_for(std::chrono::microseconds(c->test_ingest_delay_us));
   if (c->free_recorded[b] && (e = hipStreamWaitEvent(cs, c->ev_free[b], 0)) != hipSuccess) return e;
   if ((e = hipMemcpyAsync(c->staging[b], pinned_src, (size_t)nb * c->blk_bytes, hipMemcpyHostToDevice, cs)) != hipSuccess) return e;
   if (done && (e = hipEventRecord(done, cs)) != hipSuccess) return e;
   if ((e = hipEventRecord(c->ev_filled[b], cs)) != hipSuccess) return e;
   if ((e = hipStreamWaitEvent(c->s_scatter, c->ev_filled[b], 0)) != hipSuccess) return e;
+  if (c->test_scatter_delay_us > 0 && (e = launch_delay(c->test_scatter_delay_us, c->s_scatter)) != hipSuccess) return e;
   if ((e = launch_scatter_blocks(c->staging[b], pool_layer, d_table, nb, (int32_t)c->blk_bytes, 1024, c->s_scatter)) != hipSuccess) return e;
   if ((e = hipEventRecord(c->ev_free[b], c->s_scatter)) != hipSuccess) return e;
   c->free_recorded[b] = 1;
@@ -432,6 +457,11 @@ void loader_main(calvo_ctx* c, L3Job job) {
     unsigned char* pool_layer = (unsigned char*)c->cfg.pool + (int64_t)l * c->layer_bytes;
     const size_t bytes = (size_t)nb * c->blk_bytes;
     const int slot = (int)(k % (uint64_t)job.n_slots);
+    if (c->test_l3_fail_chunk >= 0 && k == (uint64_t)c->test_l3_fail_chunk) {
+      status = CALVO_EHIP;
+      err = "injected failure of the L3 loader (CALVO_TEST_L3_FAIL_CHUNK)";
+      return;
+    }
     k++;
     auto t0 = clock::now();
     if (c->l2_free_recorded[slot] && (e = hipEventSynchronize(c->ev_l2_free[slot])) != hipSuccess) {
@@ -537,6 +567,9 @@ int calvo_create(const calvo_config* cfg, calvo_ctx** out) {
     const int g = atoi(e);
     if (g >= 1 && g <= 64) c->force_splits = g;
   }
+  if (const char* e = getenv("CALVO_INGEST_DELAY_US")) { const int g = atoi(e); if (g > 0 && g <= 1000000) c->test_ingest_delay_us = g; }
+  if (const char* e = getenv("CALVO_TEST_SCATTER_DELAY_US")) { const int g = atoi(e); if (g > 0 && g <= 20000) c->test_scatter_delay_us = g; }
+  if (const char* e = getenv("CALVO_TEST_L3_FAIL_CHUNK")) { const int g = atoi(e); if (g >= 0) c->test_l3_fail_chunk = g; }
   if (const char* e = getenv("CALVO_SPLIT_MIN")) { const int g = atoi(e); if (g >= 1 && g <= 4096) c->split_min = g; }
   if (const char* e = getenv("CALVO_SPLIT_FILL")) { const int g = atoi(e); if (g >= 0 && g <= 4096) c->split_fill = g; }
   if (const char* e = getenv("CALVO_MERGE_MIB")) { const int g = atoi(e); if (g >= 0 && g <= 4096) c->merge_bytes = (size_t)g << 20; }
@@ -888,9 +921,9 @@ int calvo_chunk_event(calvo_ctx* c, int layer, int chunk, int mode, void* stream
   }
   if (chunk < 0 || chunk >= nck) return fail(CALVO_EINVAL, "chunk %d outside [0, %d) of layer %d", chunk, nck, layer);
   if (mode == CALVO_EV_QUERY) {
-    std::lock_guard<std::mutex> lk(c->mu);
+    std::unique_lock<std::mutex> lk(c->mu);
     if (c->chunks_issued[layer] <= chunk) {              // a running loader has not reached it yet
-      if (c->l3_status != CALVO_OK) { g_err = c->l3_err; return c->l3_status; }
+      if (c->l3_status != CALVO_OK) { lk.unlock(); return join_loader(c); }
       return fail(CALVO_ENOTREADY, "chunk %d of layer %d is still loading", chunk, layer);
     }
   } else {
@@ -1017,9 +1050,9 @@ int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
   if (mode != CALVO_EV_QUERY && mode != CALVO_EV_HOST_WAIT && mode != CALVO_EV_STREAM_WAIT)
     return fail(CALVO_EINVAL, "unknown mode %d", mode);
   if (mode == CALVO_EV_QUERY) {
-    std::lock_guard<std::mutex> lk(c->mu);
+    std::unique_lock<std::mutex> lk(c->mu);
     if (c->layer_pending[layer]) {
-      if (c->l3_status != CALVO_OK) { g_err = c->l3_err; return c->l3_status; }
+      if (c->l3_status != CALVO_OK) { lk.unlock(); return join_loader(c); }
       return fail(CALVO_ENOTREADY, "layer %d is still loading", layer);
     }
   } else {

@@ -54,6 +54,8 @@ struct AppendParams {
 hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_t* table, int64_t n_blocks,
                                  int32_t blk_bytes, int grid, hipStream_t stream);
 hipError_t launch_suffix_append(const AppendParams& p, hipStream_t stream);
+// test hook: occupies `stream` for about us microseconds (bounded), see kernels_ingest.hip
+hipError_t launch_delay(int us, hipStream_t stream);
 hipError_t launch_attn_simple(const AttnParams& p, int dtype, int total_tokens, hipStream_t stream);
 // The pipelined bf16 / head-dim-128 kernels (attn_pipeline.h).  The *_prepare calls raise the
 // kernels' dynamic LDS limit; once per device, before the first launch.

@@ -1,7 +1,7 @@
 // Slot bookkeeping for the paged KV space in HBM (the paper's L1 tier) with the paper's proactive
 // allocation (Section 3.1): the destination blocks of a request are reserved at the moment its
 // lower-level transfer is issued, so a block that reaches host DRAM can move on at once; when HBM is
-// short the scheme "degrades to the reactive allocation" (footnote of Section 3.1) - the request
+// short the scheme falls back to reactive allocation (footnote of Section 3.1) - the request
 // waits in a queue and gets its slots when earlier requests release theirs.  Host code only; the
 // library's loading and attention calls take the resulting block tables.  See include/calvo.h.
 #include <cstdint>

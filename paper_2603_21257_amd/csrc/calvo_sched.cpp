@@ -102,6 +102,11 @@ int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_
   if (policy < CALVO_POLICY_FIFO || policy > CALVO_POLICY_EDF) return CALVO_EINVAL;
   if ((needs_model(policy) || !load_s || !comp_s) && !model) return CALVO_EINVAL;
   if (!valid_jobs(jobs, n)) return CALVO_EINVAL;
+  if (pipelined < 0 || pipelined > 2) return CALVO_EINVAL;
+  for (int i = 0; i < n; i++) {                        // measured times must be finite and non-negative
+    if (load_s && !(load_s[i] >= 0.0 && std::isfinite(load_s[i]))) return CALVO_EINVAL;
+    if (comp_s && !(comp_s[i] >= 0.0 && std::isfinite(comp_s[i]))) return CALVO_EINVAL;
+  }
   std::vector<unsigned char> done((size_t)n, 0);
   double loader_free = -std::numeric_limits<double>::infinity();
   double compute_free = -std::numeric_limits<double>::infinity();
@@ -129,6 +134,7 @@ int calvo_sched_simulate(int policy, const calvo_cost_model* model, const calvo_
           priority_of(policy, model, jobs[i], &k.priority);
           if (best < 0 || k < bk) { best = i; bk = k; }
         }
+        if (best < 0) return CALVO_EINVAL;             // cannot happen with finite times
         finish_s[best] = t_c + (comp_s ? comp_s[best] : model_comp(*model, jobs[best]));
         compute_free = finish_s[best];
         done[best] = 1;

@@ -57,6 +57,21 @@ hipError_t launch_scatter_blocks(const void* src, void* pool_layer, const int32_
   return hipSuccess;
 }
 
+// Test hook: keeps a stream busy for about `us` microseconds (one wave that sleeps in short naps until
+// the constant 100 MHz counter has advanced; the nap count is bounded, so the wave always exits).
+__global__ void __launch_bounds__(64) delay_kernel(unsigned ticks, unsigned max_naps) {
+  const unsigned long long t0 = wall_clock64();
+  for (unsigned i = 0; i < max_naps && wall_clock64() - t0 < ticks; i++) __builtin_amdgcn_s_sleep(64);
+}
+
+hipError_t launch_delay(int us, hipStream_t stream) {
+  if (us <= 0) return hipSuccess;
+  if (us > 20000) us = 20000;
+  // a nap of s_sleep 64 lasts at least 64 * 64 cycles, i.e. more than 1.5 us at 2.4 GHz: the cap is never the limit
+  hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, stream, (unsigned)us * 100u, (unsigned)us + 16u);
+  return hipGetLastError();
+}
+
 // Suffix token i of request r sits at absolute position P_r + i: slot table_r[pos / 16],
 // row pos % 16 of the K half and of the V half.  One lane per 16-byte chunk of a row.
 __global__ void __launch_bounds__(256) suffix_append_kernel(AppendParams p) {

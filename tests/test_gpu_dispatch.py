@@ -15,7 +15,7 @@ from paper_2603_21257_amd import dispatch
 from paper_2603_21257_amd import hostmem
 from paper_2603_21257_amd import workload as wl
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.timing]
 
 
 def test_loading_aware_sjf_lowers_average_ttft_on_the_gpu():

@@ -127,11 +127,24 @@ def test_fp32_varlen_and_explicit_scale():
     check(w, scale=0.2)
 
 
-@pytest.mark.parametrize("staging_blocks,n_staging,n_copy", [(1, 2, 1), (3, 2, 2), (5, 4, 1), (64, 2, 1)])
+@pytest.mark.parametrize("staging_blocks,n_staging,n_copy", [(1, 2, 1), (3, 2, 0), (5, 4, 1), (64, 2, 1)])
 def test_staged_copy_engine_ingest_is_bit_exact(staging_blocks, n_staging, n_copy):
     shape = wl.Shape(3, 8, 2, 128, "bf16", 128)
     w = wl.make_custom(shape, [(17 * 16, 40), (9 * 16, 20)], seed=23, shared_blocks=2)
     check(w, staging_bytes=staging_blocks * shape.blk_bytes, n_staging=n_staging, n_copy_streams=n_copy)
+
+
+@pytest.mark.parametrize("hook,us", [("CALVO_TEST_SCATTER_DELAY_US", 300), ("CALVO_INGEST_DELAY_US", 200)])
+def test_staging_ring_reuse_under_adverse_timing(hook, us, monkeypatch):
+    """Two staging buffers of one block each and 26 blocks per layer: every transfer re-uses a buffer
+    that an earlier scatter has read.  With a bounded delay kernel in front of every scatter the
+    copy engine is far ahead of the scatter stream (a transfer into a buffer the scatter has not read
+    yet would show as wrong pool bytes); with the host sleeping before every transfer the scatter
+    stream runs dry between transfers instead."""
+    monkeypatch.setenv(hook, str(us))
+    shape = wl.Shape(2, 8, 2, 128, "bf16", 64)
+    w = wl.make_custom(shape, [(17 * 16, 40), (9 * 16, 20)], seed=29)
+    check(w, staging_bytes=shape.blk_bytes, n_staging=2)
 
 
 @pytest.mark.parametrize("n_layers,lens,shared,staging_blocks", [

@@ -80,6 +80,7 @@ def stack():
     s.close()
 
 
+@pytest.mark.timing
 def test_loading_time_is_linear_in_the_context_tokens(stack):
     tokens = [2048, 4096, 8192, 12288, 16384, 24576, 32768]
     secs = [stack.load_s(p) for p in tokens]
@@ -92,10 +93,11 @@ def test_loading_time_is_linear_in_the_context_tokens(stack):
     print(f"load seconds {['%.4f' % x for x in secs]} -> {per_token * 1e9:.2f} ns/token + {fixed * 1e6:.0f} us, "
           f"R^2 {r2:.5f}, slope = {rate:.1f} GB/s", flush=True)
     assert r2 > 0.995
-    assert 35.0 < rate < 70.0            # the slope is the link rate: PCIe Gen5 x16
+    assert 15.0 < rate < 80.0            # the slope is the link rate: PCIe Gen5 x16 (55-57 GB/s measured; wide margins for another box)
     assert fixed < 0.5 * secs[0]         # and the fixed part is small next to even the shortest load
 
 
+@pytest.mark.timing
 def test_ttft_falls_as_the_hit_ratio_rises(stack):
     total = 32768
     ratios = [0.25, 0.5, 0.75, 0.95, 0.998]

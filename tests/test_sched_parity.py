@@ -89,3 +89,17 @@ def test_bad_arguments_are_rejected():
         cb.calvo_cost_fit([5.0, 5.0], [1.0, 2.0])
     s, f = cb.calvo_sched_simulate(cb.CALVO_POLICY_FIFO, None, jobs, [0.1], [0.2])   # FIFO with given times: no model
     assert list(s) == [0.0] and abs(f[0] - 0.3) < 1e-15
+
+
+@pytest.mark.parametrize("pipelined", [0, 1, 2])
+def test_replay_rejects_unusable_measured_times(pipelined):
+    """Measured times that are not finite or negative, and an unknown replay mode, are refused before
+    anything is computed (a NaN loading time once left the two-stage replay without a job to pick)."""
+    jobs = [(0.0, 1.0, 10, 10), (0.1, 2.0, 20, 5)]
+    for load, comp in [([float("nan"), 0.1], [0.1, 0.1]), ([0.1, 0.1], [float("inf"), 0.1]), ([-0.1, 0.1], [0.1, 0.1])]:
+        with pytest.raises(cb.CalvoError):
+            cb.calvo_sched_simulate(cb.CALVO_POLICY_FIFO, MODEL, jobs, load, comp, pipelined)
+    with pytest.raises(cb.CalvoError):
+        cb.calvo_sched_simulate(cb.CALVO_POLICY_FIFO, MODEL, jobs, [0.1, 0.1], [0.1, 0.1], 3)
+    with pytest.raises(cb.CalvoError):
+        cb.calvo_sched_simulate(cb.CALVO_POLICY_FIFO, MODEL, jobs, [0.1, 0.1], [0.1, 0.1], -1)
