@@ -28,10 +28,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16, published
-# HBM bytes of one attention launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in
-# profiles/attn_pipe_kernel_cfg3.md (calibrated against the scatter kernel, a plain copy of known size).
-# Counters cannot be read from inside this process, so the figure is carried over from that profile.
-PROFILED_HBM_BYTES_PER_LAUNCH = {3: 654.2e6}      # attn_pipe_kernel on workload 3
+
+
+def profiled_traffic(config: int):
+    """HBM bytes of one attention launch of workload `config`, from the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE passes recorded under profiles/ (calibrated there against a plain copy of known size).
+    Counters cannot be read from inside this process: the figure is read from the profile's line
+    'HBM_BYTES_PER_LAUNCH cfg<N> = <bytes>' (None if no profile of the workload is recorded)."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        m = re.search(r"HBM_BYTES_PER_LAUNCH cfg%d = ([0-9.eE+]+)" % config, open(path).read())
+        if m:
+            return float(m.group(1))
+    return None
 
 
 def log(*a):
@@ -65,6 +75,9 @@ def main():
                          "that their attention starts on the chunks that have landed (0 = whole layers only; -1 = 4 if loading "
                          "alone takes longer than attention alone on this workload but less than twice as long, else 0)")
     ap.add_argument("--tail-layers", type=int, default=6)
+    ap.add_argument("--no-cfg4-leg", action="store_true",
+                    help="skip the short run of the attention-bound 8-request batch (workload 4) that the default run appends")
+    ap.add_argument("--leg", action="store_true", help="(internal) run as the appended leg: timing of the step only")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -262,18 +275,65 @@ def main():
             "overlap": round(overlap, 4),
             "roofline": {"bound": "mfma", "achieved": round(att_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "traffic": PROFILED_HBM_BYTES_PER_LAUNCH.get(args.config) if kernel_id == 3 and not args.custom else None,
+                         "traffic": profiled_traffic(args.config) if kernel_id == 3 and not args.custom else None,
                          "kernel": cb.ATTN_KERNEL_NAMES.get(kernel_id, f"calvo::attn_mfma_kernel (variant {kernel_id})"),
                          "workgroups_per_launch": kernel_wgs, "flop_per_launch": flop_per_launch,
                          "avg_launch_ms": round(k_ms, 4)},
         }
-        if not args.no_three_stage and w.ingest_bytes() <= (16 << 30):
+        if not args.leg:
+            # what the matrix pipes sustain on MFMAs alone (the published peak assumes the top clock; the
+            # part is power limited and the sustained rate depends on the operand data)
+            peak = measured_mfma_peak(cb, torch, dev)
+            result["mfma_measured_peak_TFLOPs"] = peak
+            result["roofline"]["frac_of_measured_mfma_peak"] = round(att_tflops / peak["normal_operands"], 4)
+        if not args.no_three_stage and not args.leg and w.ingest_bytes() <= (16 << 30):
             result["three_stage"] = three_stage(args, cb, ctx, w, host, reqs, q, ks, vs, out, poison, timed, t_att)
-        if not args.no_cpu_baseline:
+        if not args.no_cpu_baseline and not args.leg:
             result["cpu_baseline"] = cpu_baseline(w, host, q, ks, vs, out, args.sample_rows)
     finally:
         cb.calvo_destroy(ctx)
+    if not args.leg and not args.no_cfg4_leg and args.config == 3 and not args.custom and args.mode == "full":
+        # release this workload's buffers before the leg allocates its own (78 GiB pool)
+        del pool, q, ks, vs, out, host
+        arena.free()
+        torch.cuda.empty_cache()
+        result["attention_bound_leg"] = cfg4_leg()
     print(json.dumps(result), flush=True)
+
+
+def measured_mfma_peak(cb, torch, dev):
+    """calvo_mfma_peak with normally distributed and with all-zero bf16 operands."""
+    sink = torch.empty(512 * 1024, dtype=torch.float32, device=dev)
+    out = {}
+    for name, fill in (("normal_operands", lambda t: t.normal_(0.0, 1.0)), ("zero_operands", lambda t: t.zero_())):
+        ops = torch.empty(8192, dtype=torch.bfloat16, device=dev)
+        fill(ops)
+        torch.cuda.synchronize()
+        tf, ms = cb.calvo_mfma_peak(ops, sink, iters=20000, repeats=3)
+        out[name] = round(tf, 1)
+        log(f"[bench] MFMA-only peak, {name}: {tf:.0f} TFLOP/s ({ms:.2f} ms per launch)")
+    out["kernel"] = "v_mfma_f32_32x32x16_bf16 only, two waves per SIMD, register operands"
+    return out
+
+
+def cfg4_leg():
+    """The 8-request batch of workload 4 (attention bound: the step the attention kernel's speed
+    moves), 3 timed steps in a process of its own.  Extra keys of the JSON line, never `value`."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--config", "4", "--steps", "3", "--warmup", "1", "--leg"]
+    t0 = time.perf_counter()
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=600)
+    for ln in res.stderr.splitlines():
+        log("[cfg4 leg] " + ln)
+    if res.returncode != 0:
+        return {"error": f"exit code {res.returncode}"}
+    d = json.loads(res.stdout.strip().splitlines()[-1])
+    return {"workload": d["config"]["workload"], "steps": d["steps"], "ttft_ms": d["ttft_ms"]["mean"],
+            "lower_bound_ms": d["ttft_ms"]["lower_bound"], "frac_of_lower_bound": d["ttft_ms"]["frac_of_lower_bound"],
+            "ingest_alone_ms": d["ingest"]["alone_ms"], "attention_alone_ms": d["attention"]["alone_ms_all_layers"],
+            "attention_TFLOPs": d["attention"]["TFLOPs"], "frac_of_bf16_mfma_peak": d["attention"]["frac_of_bf16_mfma_peak"],
+            "avg_launch_ms": d["roofline"]["avg_launch_ms"], "kernel": d["roofline"]["kernel"],
+            "wall_s": round(time.perf_counter() - t0, 1)}
 
 
 def three_stage(args, cb, ctx, w, host, reqs, q, ks, vs, out, poison, timed, t_att):
@@ -369,13 +429,38 @@ def cpu_baseline(w, host, q, ks, vs, out, n_rows):
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     total_pairs = w.attn_pairs() * L
     extrapolated_ms = dt * 1e3 * total_pairs / max(pairs, 1)
-    log(f"[bench] oracle sample: {dt:.1f} s for {pairs} (row,key) pairs x {s.n_q_heads} heads; "
+    # the same oracle on one thread, on a sixth of the rows of the last sampled layer's first request
+    from threadpoolctl import threadpool_limits
+    r0 = next(r for r in w.requests if r.suffix_len)
+    ri0 = w.requests.index(r0)
+    a0, b0 = int(w.cu_suffix[ri0]), int(w.cu_suffix[ri0 + 1])
+    rows1 = sorted(set(rng.integers(0, r0.suffix_len, size=max(4, per_req // 6)).tolist()))
+    with threadpool_limits(limits=1):
+        t1 = time.perf_counter()
+        orc.prefill_attn_sampled(view, q_l[a0:b0], r0.table, r0.prefix_len, r0.suffix_len, B, rows1)
+        dt1 = time.perf_counter() - t1
+    pairs1 = sum(r0.prefix_len + i + 1 for i in rows1)
+    single_ms = dt1 * 1e3 * total_pairs / max(pairs1, 1)
+    cores = len(os.sched_getaffinity(0))
+    model = "unknown"
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    log(f"[bench] oracle sample: {dt:.1f} s for {pairs} (row,key) pairs x {s.n_q_heads} heads on {threads} BLAS threads "
+        f"({cores} cores in the affinity mask, {model}); one thread: {dt1:.1f} s for {pairs1} pairs; "
         f"GPU vs oracle on the sample: max-abs {worst_max:.3e}, mean-abs {max(means):.3e}")
-    return {"value": round(extrapolated_ms, 1), "unit": "ms", "cores": int(threads), "kind": "oracle",
+    return {"value": round(extrapolated_ms, 1), "unit": "ms", "cores": cores, "kind": "oracle",
+            "threads_used": int(threads), "cpu_model": model,
             "sample": f"layers {layers}, {per_req} suffix rows per request x all {s.n_q_heads} heads "
-                      f"(incl. oracle ingest + suffix append of those layers), {dt:.1f} s measured, "
+                      f"(incl. oracle ingest + suffix append of those layers), {dt:.1f} s measured on {threads} BLAS threads, "
                       f"extrapolated by unmasked (query,key) pairs to the whole step",
             "measured_s": round(dt, 2),
+            "single_thread": {"value": round(single_ms, 1), "unit": "ms", "measured_s": round(dt1, 2),
+                              "sample": f"{len(rows1)} suffix rows of one request x all heads, one layer, BLAS limited to 1 thread"},
             "gpu_vs_oracle_on_sample": {"max_abs": worst_max, "mean_abs": max(means)}}
 
 
