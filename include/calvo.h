@@ -238,6 +238,25 @@ int calvo_layer_event(calvo_ctx* ctx, int layer, int mode, void* stream);
 int calvo_prefill_attn(calvo_ctx* ctx, int layer, const void* q, const void* k_suffix, const void* v_suffix,
                        void* out, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale);
 
+/* A batch prepared once for all its layers.  calvo_prefill_attn validates the requests, plans the launch
+ * and describes it to the device on every call; a prefill runs the same batch through every layer, so
+ * calvo_batch_prepare does all of that once: it checks reqs / cu_suffix as calvo_prefill_attn does,
+ * copies the block tables, decides the launch (kernel, tiles, split-KV pieces) and uploads the
+ * descriptors to a device buffer of its own (queued on the compute stream).  calvo_prefill_attn_batch
+ * then only queues the layer's work - the wait for the layer's blocks, the suffix append, the
+ * attention - with the result of calvo_prefill_attn for the same arguments.  Several batches can be
+ * alive and queued at once (each has its own descriptors).  A layer that was loaded in chunks gets its
+ * chunk-following launches planned the first time that chunking is seen and kept with the batch.
+ * calvo_batch_destroy waits for the compute stream (launches may still read the descriptors) and
+ * frees the batch - its descriptor buffers go back to the context, which hands them to later batches
+ * and frees them in calvo_destroy; it must precede calvo_destroy of its context.  Errors: as calvo_prefill_attn; CALVO_ENOMEM / CALVO_EHIP if the
+ * descriptor buffers cannot be had (nothing is leaked). */
+typedef struct calvo_batch calvo_batch;
+int calvo_batch_prepare(calvo_ctx* ctx, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, calvo_batch** out);
+int calvo_batch_destroy(calvo_batch* batch);
+int calvo_prefill_attn_batch(calvo_ctx* ctx, calvo_batch* batch, int layer, const void* q, const void* k_suffix,
+                             const void* v_suffix, void* out, float scale);
+
 /* The same operation for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, result and errors are
  * those of calvo_prefill_attn; the call itself allocates nothing (no hipMalloc / hipFree / pinned
@@ -348,6 +367,107 @@ int calvo_pool_admit(calvo_pool* pool, const int32_t* shared, int32_t n_shared, 
 int calvo_pool_retry(calvo_pool* pool, int64_t ticket, int32_t* table);
 /* Withdraws a queued admission and gives back its references on the shared run. */
 int calvo_pool_cancel(calvo_pool* pool, int64_t ticket);
+
+/* ---- The multi-request dispatcher (paper Section 3.1: each loading stage and the compute stage has a
+ * dispatcher and an executor of its own and the stages run concurrently on different requests; a
+ * block moves up one level only if it has arrived from the level below and its destination is
+ * allocated; the destination is requested when the lower-level transfer is issued, and when HBM is
+ * short the allocation is made reactively; Section 3.2: every stage serves its queue in the order of
+ * the scheduling policy).
+ *
+ * The dispatcher owns one thread per stage:
+ *   link   (three_stage != 0) L3 -> L2: takes the highest-priority submitted job, requests its HBM
+ *          slots from `pool` (calvo_pool_admit) and streams its blocks, layer by layer in chunks, from
+ *          the job's pageable host_kv through the pinned ring at no more than l3.l3_GBps;
+ *   pcie   L2 -> L1: three_stage: takes the landed chunks in link order; a chunk moves on when it is in
+ *          the ring and its job's slots are granted - a job the pool could not admit at once waits
+ *          here (calvo_pool_retry, woken by calvo_dispatch_release), its chunks held in the ring and
+ *          the link stalling behind them.  three_stage == 0: the jobs' host_kv is page-locked host
+ *          memory, the stage picks the highest-priority job when the previous job's last block has
+ *          landed, admits it (waiting here if HBM is short) and queues its layers;
+ *   compute  takes the highest-priority job whose first layer has been handed over, and queues
+ *          suffix append + attention of every layer on the compute stream, each behind the event of
+ *          its layer's last block (a per-job event set: jobs loading at the same time do not share
+ *          readiness state);
+ *   done   waits for each job's last launch and stamps its first-token time.
+ * A job's data: q, k_suffix, v_suffix, out are DEVICE arrays over all layers ([L][S][H][D], layer l at
+ * l times the layer stride, 16-byte aligned); k_suffix / v_suffix may be NULL (suffix K/V already in
+ * the pool).  host_kv / host_layer_stride as in calvo_request, for blocks
+ * [n_shared, n_prefix_blocks).  Without a pool, block_table holds all n_prefix_blocks +
+ * ceil(suffix_len/16) slots; with a pool it holds the n_shared slots of a run that is already resident
+ * and in use, and the dispatcher obtains the rest.  All job memory stays valid until the job has
+ * finished; block_table is copied by submit.  While a dispatcher is alive it is the only user of its
+ * context.  With ctx == NULL the dispatcher is a dry run of the stage logic on the host clock: the
+ * loading stage is busy sim_load_s per job, the compute stage sim_comp_s, with the same queues,
+ * policy and admission; no device is touched. */
+typedef struct calvo_dispatcher calvo_dispatcher;
+
+typedef struct {
+  int32_t policy;             /* CALVO_POLICY_*: the order every stage serves its queue in */
+  int32_t three_stage;        /* != 0: emulated L3 link in front (pageable host_kv); 0: host_kv is pinned */
+  calvo_cost_model model;     /* for SJF / LSTF priorities */
+  calvo_l3_config l3;         /* three_stage: ring and link rate (chunk_ready is ignored) */
+  calvo_pool* pool;           /* HOST, may be NULL: the caller assigns all slots itself */
+} calvo_dispatch_config;
+
+typedef struct {
+  const void* host_kv;        /* HOST */
+  int64_t host_layer_stride;
+  const int32_t* block_table; /* HOST */
+  int32_t n_prefix_blocks, n_shared, suffix_len, reserved;
+  const void* q;              /* DEVICE */
+  const void* k_suffix;       /* DEVICE or NULL */
+  const void* v_suffix;       /* DEVICE or NULL */
+  void* out;                  /* DEVICE */
+  int64_t q_layer_stride;     /* bytes from layer l to layer l+1 of q; 0 = dense (suffix_len * Hq * D elements) */
+  int64_t kv_layer_stride;    /* the same for k_suffix / v_suffix; 0 = dense (suffix_len * Hkv * D elements) */
+  int64_t out_layer_stride;   /* the same for out; 0 = dense (suffix_len * Hq * D elements) */
+  float scale;                /* <= 0: 1/sqrt(D) */
+  float reserved2;
+  double deadline_s;          /* TTFT deadline relative to submission (LSTF, EDF); <= 0: none */
+  double sim_load_s, sim_comp_s; /* dry run only */
+} calvo_dispatch_job;
+
+typedef struct {              /* times in seconds since calvo_dispatch_create */
+  double submit_s, load_start_s, load_end_s, compute_start_s, first_token_s;
+  double alloc_wait_s;        /* time the job's blocks waited below for HBM slots (reactive allocation) */
+  int32_t reactive;           /* != 0: the pool could not grant the slots when the transfer was issued */
+  int32_t status;             /* CALVO_OK or the error that stopped the job */
+} calvo_dispatch_result;
+
+typedef struct {
+  double  link_busy_s;        /* three_stage: time the emulated link was occupied (copy + throttle) */
+  double  link_span_s;        /* from its first chunk's start to its last chunk's end */
+  double  ring_wait_s;        /* time the link waited for a free ring slot */
+  int64_t bytes;              /* bytes moved over the link */
+  int64_t jobs_submitted, jobs_done;
+} calvo_dispatch_stats;
+
+/* Starts the stage threads.  ctx needs staging buffers.  CALVO_EINVAL for bad config fields,
+ * CALVO_ENOMEM / CALVO_EHIP if the pinned ring or the threads cannot be had. */
+int calvo_dispatch_create(calvo_ctx* ctx, const calvo_dispatch_config* cfg, calvo_dispatcher** out);
+/* Queues a job; *id identifies it (ids count from 0 in submission order).  Returns at once.
+ * CALVO_EINVAL (nothing queued) for bad counts or NULL pointers that the job needs, a host_kv that
+ * is not page-locked in two-stage mode; CALVO_ENOMEM if the job can never fit the pool. */
+int calvo_dispatch_submit(calvo_dispatcher* d, const calvo_dispatch_job* job, int64_t* id);
+/* Blocks until the job's last attention launch has finished (its first token could be sampled) or the
+ * job has failed; returns the job's status and fills res (may be NULL). */
+int calvo_dispatch_wait(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* res);
+/* The same without blocking: CALVO_ENOTREADY while the job is under way (res holds what is known). */
+int calvo_dispatch_poll(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* res);
+/* The job's block table (shared run, then its own slots): *n entries into table[0..capacity).
+ * CALVO_ENOTREADY before the slots are granted, CALVO_ENOMEM if capacity is too small (*n is set). */
+int calvo_dispatch_table(calvo_dispatcher* d, int64_t id, int32_t* table, int32_t capacity, int32_t* n);
+/* The request has left the GPU (its decode is over): gives its slots back to the pool - one reference
+ * per table entry - and wakes the jobs that wait for slots.  Only after the job has finished
+ * (CALVO_ENOTREADY before), once per job.  Jobs that wait for HBM make progress only through this
+ * call: a caller that uses a pool smaller than its working set must release finished jobs. */
+int calvo_dispatch_release(calvo_dispatcher* d, int64_t id);
+int calvo_dispatch_stats_get(calvo_dispatcher* d, calvo_dispatch_stats* stats);
+/* Waits for every submitted job to finish - jobs that wait for slots need calvo_dispatch_release from
+ * another thread, or this call does not return - stops the threads, waits for the streams, gives back
+ * the slots of jobs that were not released, and frees the dispatcher.  Must precede calvo_destroy. */
+int calvo_dispatch_destroy(calvo_dispatcher* d);
 
 /* Measurement helper: duration in milliseconds of the most recent attention kernel queued by
  * calvo_prefill_attn for `layer` (HIP events recorded around the kernel on the compute

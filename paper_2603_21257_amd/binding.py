@@ -23,10 +23,12 @@ CALVO_EV_QUERY, CALVO_EV_HOST_WAIT, CALVO_EV_STREAM_WAIT = 0, 1, 2
 # CALVO_LIB names another build of the library (A/B timing of two builds); default: the in-tree one
 LIB_PATH = os.environ.get("CALVO_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcalvo.so")
 EXPORTS = ["calvo_create", "calvo_destroy", "calvo_kv_ingest", "calvo_kv_ingest_chunked", "calvo_chunk_count",
-           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_prefill_attn_noalloc", "calvo_attn_kernel_ms", "calvo_mfma_peak", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
+           "calvo_chunk_event", "calvo_kv_ingest_l3", "calvo_l3_wait", "calvo_layer_event", "calvo_prefill_attn", "calvo_prefill_attn_noalloc", "calvo_batch_prepare", "calvo_batch_destroy", "calvo_prefill_attn_batch", "calvo_attn_kernel_ms", "calvo_mfma_peak", "calvo_attn_kernel_info", "calvo_attn_plan", "calvo_attn_plan_items", "calvo_ingest_plan", "calvo_cost_fit", "calvo_cost_estimate",
            "calvo_sched_pick", "calvo_sched_simulate", "calvo_pool_create", "calvo_pool_destroy", "calvo_pool_reserve",
            "calvo_pool_retain", "calvo_pool_release", "calvo_pool_counts", "calvo_pool_admit", "calvo_pool_retry",
-           "calvo_pool_cancel", "calvo_last_error"]
+           "calvo_pool_cancel", "calvo_dispatch_create", "calvo_dispatch_submit", "calvo_dispatch_wait", "calvo_dispatch_poll",
+           "calvo_dispatch_table", "calvo_dispatch_release", "calvo_dispatch_stats_get", "calvo_dispatch_destroy",
+           "calvo_last_error"]
 CALVO_POLICY_FIFO, CALVO_POLICY_SJF, CALVO_POLICY_SJF_PT, CALVO_POLICY_LSTF, CALVO_POLICY_EDF = range(5)
 
 
@@ -62,6 +64,30 @@ class calvo_job(C.Structure):
                 ("query_tokens", C.c_int64)]
 
 
+class calvo_dispatch_config(C.Structure):
+    _fields_ = [("policy", C.c_int32), ("three_stage", C.c_int32), ("model", calvo_cost_model), ("l3", calvo_l3_config),
+                ("pool", C.c_void_p)]
+
+
+class calvo_dispatch_job(C.Structure):
+    _fields_ = [("host_kv", C.c_void_p), ("host_layer_stride", C.c_int64), ("block_table", C.POINTER(C.c_int32)),
+                ("n_prefix_blocks", C.c_int32), ("n_shared", C.c_int32), ("suffix_len", C.c_int32), ("reserved", C.c_int32),
+                ("q", C.c_void_p), ("k_suffix", C.c_void_p), ("v_suffix", C.c_void_p), ("out", C.c_void_p),
+                ("q_layer_stride", C.c_int64), ("kv_layer_stride", C.c_int64), ("out_layer_stride", C.c_int64), ("scale", C.c_float), ("reserved2", C.c_float), ("deadline_s", C.c_double), ("sim_load_s", C.c_double),
+                ("sim_comp_s", C.c_double)]
+
+
+class calvo_dispatch_result(C.Structure):
+    _fields_ = [("submit_s", C.c_double), ("load_start_s", C.c_double), ("load_end_s", C.c_double),
+                ("compute_start_s", C.c_double), ("first_token_s", C.c_double), ("alloc_wait_s", C.c_double),
+                ("reactive", C.c_int32), ("status", C.c_int32)]
+
+
+class calvo_dispatch_stats(C.Structure):
+    _fields_ = [("link_busy_s", C.c_double), ("link_span_s", C.c_double), ("ring_wait_s", C.c_double), ("bytes", C.c_int64),
+                ("jobs_submitted", C.c_int64), ("jobs_done", C.c_int64)]
+
+
 class CalvoError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"calvo error {code}: {msg}")
@@ -93,6 +119,10 @@ def lib() -> C.CDLL:
         L.calvo_prefill_attn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.c_float]
         L.calvo_prefill_attn_noalloc.argtypes = L.calvo_prefill_attn.argtypes
+        L.calvo_batch_prepare.argtypes = [C.c_void_p, C.POINTER(calvo_request), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_void_p)]
+        L.calvo_batch_destroy.argtypes = [C.c_void_p]
+        L.calvo_prefill_attn_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                               C.c_float]
         L.calvo_mfma_peak.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
         L.calvo_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
@@ -119,6 +149,14 @@ def lib() -> C.CDLL:
         L.calvo_pool_admit.argtypes = [C.c_void_p, i32p, C.c_int32, C.c_int32, i32p, i64p]
         L.calvo_pool_retry.argtypes = [C.c_void_p, C.c_int64, i32p]
         L.calvo_pool_cancel.argtypes = [C.c_void_p, C.c_int64]
+        L.calvo_dispatch_create.argtypes = [C.c_void_p, C.POINTER(calvo_dispatch_config), C.POINTER(C.c_void_p)]
+        L.calvo_dispatch_submit.argtypes = [C.c_void_p, C.POINTER(calvo_dispatch_job), i64p]
+        L.calvo_dispatch_wait.argtypes = [C.c_void_p, C.c_int64, C.POINTER(calvo_dispatch_result)]
+        L.calvo_dispatch_poll.argtypes = [C.c_void_p, C.c_int64, C.POINTER(calvo_dispatch_result)]
+        L.calvo_dispatch_table.argtypes = [C.c_void_p, C.c_int64, i32p, C.c_int32, i32p]
+        L.calvo_dispatch_release.argtypes = [C.c_void_p, C.c_int64]
+        L.calvo_dispatch_stats_get.argtypes = [C.c_void_p, C.POINTER(calvo_dispatch_stats)]
+        L.calvo_dispatch_destroy.argtypes = [C.c_void_p]
         L.calvo_last_error.argtypes = []
         L.calvo_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -240,6 +278,22 @@ def calvo_prefill_attn_noalloc(ctx: int, layer: int, q, k_suffix, v_suffix, out,
     _check(lib().calvo_prefill_attn_noalloc(ctx, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out),
                                             _req_array(reqs), len(reqs), cu.ctypes.data_as(C.POINTER(C.c_int32)),
                                             float(scale)))
+
+
+def calvo_batch_prepare(ctx: int, reqs: Sequence[calvo_request], cu_suffix: np.ndarray) -> int:
+    """Validates, plans and uploads the batch once; returns the handle for calvo_prefill_attn_batch."""
+    cu = np.ascontiguousarray(cu_suffix, dtype=np.int32)
+    out = C.c_void_p()
+    _check(lib().calvo_batch_prepare(ctx, _req_array(reqs), len(reqs), cu.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(out)))
+    return out.value
+
+
+def calvo_batch_destroy(batch: int) -> None:
+    _check(lib().calvo_batch_destroy(batch))
+
+
+def calvo_prefill_attn_batch(ctx: int, batch: int, layer: int, q, k_suffix, v_suffix, out, scale: float = 0.0) -> None:
+    _check(lib().calvo_prefill_attn_batch(ctx, batch, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out), float(scale)))
 
 
 def calvo_mfma_peak(operands, sink, iters: int = 20000, repeats: int = 3):
@@ -441,3 +495,73 @@ def calvo_pool_retry(pool: int, ticket: int, n_table: int):
 
 def calvo_pool_cancel(pool: int, ticket: int) -> None:
     _pool_check(lib().calvo_pool_cancel(pool, ticket))
+
+
+# ---- the multi-request dispatcher (stage threads inside the library)
+
+def _fields(st) -> dict:
+    return {name: getattr(st, name) for name, _ in st._fields_}
+
+
+def calvo_dispatch_create(ctx: Optional[int], policy: int, model=None, three_stage: bool = False, pool: int = 0,
+                          chunk_bytes: int = 0, n_slots: int = 0, n_threads: int = 0, l3_GBps: float = 0.0) -> int:
+    """ctx None: a dry run of the stage logic (jobs carry sim_load_s / sim_comp_s).  Returns the handle."""
+    cfg = calvo_dispatch_config(int(policy), 1 if three_stage else 0, calvo_cost_model(*(model or (0.0, 0.0, 0.0, 0.0))),
+                                calvo_l3_config(int(chunk_bytes), int(n_slots), int(n_threads), float(l3_GBps), 0, 0),
+                                pool or None)
+    out = C.c_void_p()
+    _check(lib().calvo_dispatch_create(ctx, C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def calvo_dispatch_submit(d: int, host_kv=None, host_layer_stride: int = 0, block_table=(), n_prefix_blocks: int = 0,
+                          n_shared: int = 0, suffix_len: int = 0, q=None, k_suffix=None, v_suffix=None, out=None,
+                          scale: float = 0.0, deadline_s: float = 0.0, sim_load_s: float = 0.0, sim_comp_s: float = 0.0,
+                          q_layer_stride: int = 0, kv_layer_stride: int = 0, out_layer_stride: int = 0) -> int:
+    """Queues one job (q, k_suffix, v_suffix, out: [L][S][H][D] device arrays) and returns its id."""
+    tab, tp = _i32(block_table)
+    job = calvo_dispatch_job(_ptr(host_kv), int(host_layer_stride), tp if len(tab) else None, int(n_prefix_blocks), int(n_shared),
+                             int(suffix_len), 0, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out), int(q_layer_stride), int(kv_layer_stride), int(out_layer_stride),
+                             float(scale), 0.0,
+                             float(deadline_s), float(sim_load_s), float(sim_comp_s))
+    jid = C.c_int64(-1)
+    _check(lib().calvo_dispatch_submit(d, C.byref(job), C.byref(jid)))
+    return jid.value
+
+
+def calvo_dispatch_wait(d: int, job: int) -> dict:
+    res = calvo_dispatch_result()
+    _check(lib().calvo_dispatch_wait(d, job, C.byref(res)))
+    return _fields(res)
+
+
+def calvo_dispatch_poll(d: int, job: int):
+    """The job's result once it has finished, else None."""
+    res = calvo_dispatch_result()
+    rc = _check(lib().calvo_dispatch_poll(d, job, C.byref(res)), ok=(CALVO_OK, CALVO_ENOTREADY))
+    return _fields(res) if rc == CALVO_OK else None
+
+
+def calvo_dispatch_table(d: int, job: int) -> np.ndarray:
+    n = C.c_int32(0)
+    rc = lib().calvo_dispatch_table(d, job, None, 0, C.byref(n))
+    if rc not in (CALVO_OK, CALVO_ENOMEM):
+        _check(rc)
+    table, tp = _i32(np.zeros(max(n.value, 1)))
+    if n.value:
+        _check(lib().calvo_dispatch_table(d, job, tp, n.value, C.byref(n)))
+    return table[:n.value].copy()
+
+
+def calvo_dispatch_release(d: int, job: int) -> None:
+    _check(lib().calvo_dispatch_release(d, job))
+
+
+def calvo_dispatch_stats_get(d: int) -> dict:
+    st = calvo_dispatch_stats()
+    _check(lib().calvo_dispatch_stats_get(d, C.byref(st)))
+    return _fields(st)
+
+
+def calvo_dispatch_destroy(d: int) -> None:
+    _check(lib().calvo_dispatch_destroy(d))

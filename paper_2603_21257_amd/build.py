@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcalvo.so")
-SOURCES = ["calvo_api.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_pipe.hip", "attn_duo.hip", "mfma_peak.hip", "attn_plan.cpp", "ingest_plan.cpp", "calvo_sched.cpp", "calvo_pool.cpp"]
+SOURCES = ["calvo_api.hip", "calvo_dispatch.hip", "kernels_ingest.hip", "attn_simple.hip", "attn_pipe.hip", "attn_duo.hip", "mfma_peak.hip", "attn_plan.cpp", "ingest_plan.cpp", "calvo_sched.cpp", "calvo_pool.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-fno-gpu-rdc"]

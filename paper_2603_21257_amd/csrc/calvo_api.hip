@@ -16,15 +16,18 @@
 #include <thread>
 #include <vector>
 
-#include "../../include/calvo.h"
-#include "calvo_internal.h"
+#include "calvo_ctx.h"
 #include "ingest_plan.h"
 
 using namespace calvo;
+using namespace calvo::host;
 
 namespace {
-
 thread_local std::string g_err;
+}
+
+namespace calvo {
+namespace host {
 
 int fail(int code, const char* fmt, ...) {
   char buf[512];
@@ -41,11 +44,10 @@ int fail_hip(hipError_t e, const char* what) {
   return fail(e == hipErrorOutOfMemory ? CALVO_ENOMEM : CALVO_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-#define HIP_TRY(expr)                                  \
-  do {                                                 \
-    hipError_t e_ = (expr);                            \
-    if (e_ != hipSuccess) return fail_hip(e_, #expr);  \
-  } while (0)
+}  // namespace host
+}  // namespace calvo
+
+namespace {
 
 // ---- device memory for calvo_prefill_attn_noalloc: what calvo_prefill_attn keeps in buffers it
 // allocates (the descriptor blob and the split-KV partial results) lives here in one file-scope
@@ -88,91 +90,6 @@ int scratch_for_device(int dev, unsigned char** out) {
 
 }  // namespace
 
-struct calvo_ctx {
-  calvo_config cfg{};
-  size_t elt = 0, blk_bytes = 0;
-  int64_t layer_bytes = 0;
-  int n_staging = 0, n_copy = 0;
-  int64_t staging_blocks = 0;
-  hipStream_t s_copy[1] = {nullptr};
-  hipStream_t s_scatter = nullptr;
-  hipStream_t s_compute = nullptr;
-  bool own_compute = false;
-  std::vector<void*> staging;
-  std::vector<hipEvent_t> ev_filled, ev_free;
-  std::vector<char> free_recorded;
-  uint64_t seq = 0;
-  std::vector<hipEvent_t> ev_layer;
-  std::vector<char> layer_issued;
-  // chunk-granular readiness: layer l was loaded in pieces of chunk_blocks[l] block indices
-  // (0 = as a whole); ev_chunk[l][k] fires when blocks [0, (k+1) * chunk_blocks[l]) of every
-  // request are resident
-  std::vector<int32_t> chunk_blocks;
-  std::vector<int32_t> n_chunks;
-  std::vector<int32_t> chunks_issued;   // chunk events recorded so far (a running loader records them one by one; guarded by mu)
-  std::vector<std::vector<hipEvent_t>> ev_chunk;
-  // ingest-side table copy (device) and its pinned shadow
-  int32_t* d_tab_ing = nullptr;
-  int32_t* h_tab_ing = nullptr;
-  size_t tab_ing_cap = 0;
-  hipEvent_t ev_tab_ing = nullptr;
-  bool tab_ing_pending = false;
-  // attention-side descriptor blob: [ReqDesc x n][WorkItem x m][tables]
-  int32_t* d_att = nullptr;
-  // its pinned shadows: an upload reads its shadow when the compute stream gets to it, so a batch that
-  // differs from the previous one takes the next shadow instead of waiting for that upload (several
-  // requests can be queued on the compute stream without the calling thread blocking)
-  static constexpr int kShadows = 4;
-  int32_t* h_att[kShadows] = {nullptr, nullptr, nullptr, nullptr};
-  size_t att_cap = 0;     // in int32
-  size_t att_len = 0;     // valid int32 in shadow att_cur == on device
-  int att_cur = 0;
-  hipEvent_t ev_att[kShadows] = {nullptr, nullptr, nullptr, nullptr};
-  bool att_pending[kShadows] = {false, false, false, false};
-  std::vector<hipEvent_t> ev_t0, ev_t1;
-  std::vector<char> timed;
-  std::vector<int32_t> last_variant, last_wgs;   // per layer: attention kernel chosen, workgroups launched
-  int scatter_grid = 64;
-  size_t merge_bytes = (size_t)256 << 20;   // consecutive small layers cross PCIe together up to this size (CALVO_MERGE_MIB)
-  int force_splits = 0;           // CALVO_ATTN_SPLITS: pieces per tile (0 = automatic)
-  int split_min = 48;             // shortest piece of a cut tile, in 32-key sub-tiles
-  int split_fill = 30;            // cost of a workgroup's pipeline fill and drain, in sub-tile steps (launch replay)
-  int n_cus = 256;                // compute units of the device
-  std::vector<int64_t> plan_key;  // lengths of the batch the cached decision belongs to
-  int plan_want = 1;
-  float* part_o = nullptr;        // split-KV partial results (compute stream only)
-  float* part_ml = nullptr;
-  size_t part_slots = 0;          // capacity in (work item, head group, wave) slots
-  int device = 0;
-  // test hooks (environment, read by calvo_create): the host sleeps this long before it queues each
-  // transfer of the L2 -> L1 stage (makes the loading stage the slow one without touching the
-  // device); the L3 loader reports a failure instead of moving chunk number test_l3_fail_chunk
-  int test_ingest_delay_us = 0;
-  int test_scatter_delay_us = 0;     // a delay kernel in front of every scatter: the scatter becomes the slow stage
-  int test_l3_fail_chunk = -1;
-  // ---- calvo_prefill_attn_noalloc: this device's static array and pinned shadows of fixed size
-  // (made by calvo_create) for the descriptor uploads
-  unsigned char* d_static = nullptr;
-  int32_t* h_static[kShadows] = {nullptr, nullptr, nullptr, nullptr};
-  hipEvent_t ev_static[kShadows] = {nullptr, nullptr, nullptr, nullptr};
-  bool static_pending[kShadows] = {false, false, false, false};
-  int static_cur = 0;
-  // ---- emulated L3 -> L2 stage: a loader thread, a ring of pinned buffers, and the hand-over
-  // state it shares with the calling thread (layer_issued, l3_*: guarded by mu)
-  std::mutex mu;
-  std::condition_variable cv;
-  std::thread loader;
-  bool loader_started = false;
-  std::vector<char> layer_pending;           // layers a running loader will still hand over
-  int l3_status = CALVO_OK;
-  std::string l3_err;
-  calvo_l3_stats l3_stats{};
-  std::vector<void*> l2_ring;
-  std::vector<hipEvent_t> ev_l2_free;
-  std::vector<char> l2_free_recorded;
-  size_t l2_slot_bytes = 0;
-};
-
 namespace {
 
 void destroy_partial(calvo_ctx* c) {
@@ -199,6 +116,7 @@ void destroy_partial(calvo_ctx* c) {
   for (auto e : c->ev_static) if (e) (void)hipEventDestroy(e);
   if (c->part_o) (void)hipFree(c->part_o);
   if (c->part_ml) (void)hipFree(c->part_ml);
+  for (auto& b : c->blob_free) { (void)hipFree(b.d); (void)hipHostFree(b.h); }
   for (auto& s : c->s_copy) if (s) (void)hipStreamDestroy(s);
   if (c->s_scatter) (void)hipStreamDestroy(c->s_scatter);
   if (c->own_compute && c->s_compute) (void)hipStreamDestroy(c->s_compute);
@@ -228,6 +146,11 @@ int validate_config(const calvo_config* cfg) {
     return fail(CALVO_EINVAL, "staging_bytes (%zu) is smaller than one block (%zu)", cfg->staging_bytes, blk);
   return CALVO_OK;
 }
+
+}  // namespace
+
+namespace calvo {
+namespace host {
 
 // Checks shared by ingest and attention.  Nothing is queued before these pass.
 int validate_requests(const calvo_ctx* c, const calvo_request* reqs, int n_reqs, bool need_host,
@@ -266,6 +189,11 @@ int validate_requests(const calvo_ctx* c, const calvo_request* reqs, int n_reqs,
   }
   return CALVO_OK;
 }
+
+}  // namespace host
+}  // namespace calvo
+
+namespace {
 
 int ensure_ing_table(calvo_ctx* c, size_t n) {
   if (n <= c->tab_ing_cap) return CALVO_OK;
@@ -383,6 +311,11 @@ bool layer_is_issued(calvo_ctx* c, int layer) {
   return c->layer_issued[layer] != 0;
 }
 
+}  // namespace
+
+namespace calvo {
+namespace host {
+
 // L2->L1 for nb consecutive blocks (nb <= staging_blocks) that sit in page-locked host memory:
 // copy engine into the next device staging buffer, then scatter into the pool through the table.
 // If done is given it is recorded on the copy stream right after the transfer (the source may be
@@ -406,6 +339,11 @@ hipError_t enqueue_staged(calvo_ctx* c, const unsigned char* pinned_src, unsigne
   return hipSuccess;
 }
 
+}  // namespace host
+}  // namespace calvo
+
+namespace {
+
 struct L3Request {            // what the loader keeps of a calvo_request after the call has returned
   const unsigned char* src;   // pageable "remote" memory
   int64_t layer_stride;
@@ -422,6 +360,11 @@ struct L3Job {
   double rate = 0.0;          // bytes per second, 0 = unthrottled
 };
 
+}  // namespace
+
+namespace calvo {
+namespace host {
+
 void parallel_copy(unsigned char* dst, const unsigned char* src, size_t n, int n_threads) {
   size_t piece = (n / (size_t)n_threads + 4095) & ~(size_t)4095;
   if (piece == 0 || n_threads <= 1 || n <= piece) {
@@ -434,6 +377,11 @@ void parallel_copy(unsigned char* dst, const unsigned char* src, size_t n, int n
   memcpy(dst, src, piece);
   for (auto& t : th) t.join();
 }
+
+}  // namespace host
+}  // namespace calvo
+
+namespace {
 
 // Body of the loader thread: L3 -> L2 (host copy into the pinned ring, rate limited), then the
 // hand-over of every landed chunk to the L2 -> L1 stage.
@@ -658,6 +606,47 @@ int calvo_destroy(calvo_ctx* c) {
 
 namespace {
 
+}  // namespace
+
+namespace calvo {
+namespace host {
+
+int upload_ingest_table(calvo_ctx* c, const int32_t* slots, size_t n) {
+  if (n == 0) return CALVO_OK;
+  int rc = ensure_ing_table(c, n);
+  if (rc != CALVO_OK) return rc;
+  // the pinned shadow is read when the scatter stream gets to the previous upload
+  if (c->tab_ing_pending) { HIP_TRY(hipEventSynchronize(c->ev_tab_ing)); c->tab_ing_pending = false; }
+  memcpy(c->h_tab_ing, slots, n * 4);
+  HIP_TRY(hipMemcpyAsync(c->d_tab_ing, c->h_tab_ing, n * 4, hipMemcpyHostToDevice, c->s_scatter));
+  HIP_TRY(hipEventRecord(c->ev_tab_ing, c->s_scatter));
+  c->tab_ing_pending = true;
+  return CALVO_OK;
+}
+
+int ensure_l2_ring(calvo_ctx* c, size_t slot_bytes, int n_slots) {
+  if (slot_bytes <= c->l2_slot_bytes && (int)c->l2_ring.size() >= n_slots) return CALVO_OK;
+  for (auto& s : c->s_copy) if (s) HIP_TRY(hipStreamSynchronize(s));
+  for (void* p : c->l2_ring) if (p) (void)hipHostFree(p);
+  for (auto e : c->ev_l2_free) if (e) (void)hipEventDestroy(e);
+  c->l2_ring.assign(n_slots, nullptr);
+  c->ev_l2_free.assign(n_slots, nullptr);
+  c->l2_free_recorded.assign(n_slots, 0);
+  c->l2_slot_bytes = 0;
+  for (int i = 0; i < n_slots; i++) {
+    hipError_t e = hipHostMalloc(&c->l2_ring[i], slot_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_l2_free[i], hipEventDisableTiming);
+    if (e != hipSuccess) return fail_hip(e, "pinned L2 ring");
+  }
+  c->l2_slot_bytes = slot_bytes;
+  return CALVO_OK;
+}
+
+}  // namespace host
+}  // namespace calvo
+
+namespace {
+
 // Front part shared by both ingest calls: validation, source pointers, block tables to the device.
 // pinned: the sources must be page-locked (and device-mapped for the zero-copy mode).
 int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int layer_begin, int layer_end, bool pinned,
@@ -700,16 +689,13 @@ int prepare_ingest(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int laye
   if (layer_begin == layer_end || n_reqs == 0) return CALVO_OK;
   // block tables -> device (ingest stream)
   if (n_tab > 0) {
-    rc = ensure_ing_table(c, n_tab);
-    if (rc != CALVO_OK) return rc;
-    if (c->tab_ing_pending) { HIP_TRY(hipEventSynchronize(c->ev_tab_ing)); c->tab_ing_pending = false; }
+    std::vector<int32_t> slots(n_tab);
     for (int r = 0; r < n_reqs; r++)
       if (reqs[r].n_prefix_blocks > reqs[r].first_ingest_block)
-        memcpy(c->h_tab_ing + tab_off[r] + reqs[r].first_ingest_block, reqs[r].block_table + reqs[r].first_ingest_block,
+        memcpy(slots.data() + tab_off[r] + reqs[r].first_ingest_block, reqs[r].block_table + reqs[r].first_ingest_block,
                (size_t)(reqs[r].n_prefix_blocks - reqs[r].first_ingest_block) * 4);
-    HIP_TRY(hipMemcpyAsync(c->d_tab_ing, c->h_tab_ing, n_tab * 4, hipMemcpyHostToDevice, c->s_scatter));
-    HIP_TRY(hipEventRecord(c->ev_tab_ing, c->s_scatter));
-    c->tab_ing_pending = true;
+    rc = upload_ingest_table(c, slots.data(), n_tab);
+    if (rc != CALVO_OK) return rc;
   }
   return CALVO_OK;
 }
@@ -988,22 +974,8 @@ int calvo_kv_ingest_l3(calvo_ctx* c, const calvo_request* reqs, int n_reqs, int 
       job.reqs.push_back({src[r], reqs[r].host_layer_stride, reqs[r].first_ingest_block, reqs[r].n_prefix_blocks, tab_off[r]});
 
   // the pinned ring (kept for later calls; regrown if a call asks for more)
-  const size_t slot_bytes = (size_t)job.chunk_blocks * c->blk_bytes;
-  if (slot_bytes > c->l2_slot_bytes || (int)c->l2_ring.size() < job.n_slots) {
-    for (auto& s : c->s_copy) if (s) HIP_TRY(hipStreamSynchronize(s));
-    for (void* p : c->l2_ring) if (p) (void)hipHostFree(p);
-    for (auto e : c->ev_l2_free) if (e) (void)hipEventDestroy(e);
-    c->l2_ring.assign(job.n_slots, nullptr);
-    c->ev_l2_free.assign(job.n_slots, nullptr);
-    c->l2_free_recorded.assign(job.n_slots, 0);
-    c->l2_slot_bytes = 0;
-    for (int i = 0; i < job.n_slots; i++) {
-      hipError_t e = hipHostMalloc(&c->l2_ring[i], slot_bytes, hipHostMallocDefault);
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_l2_free[i], hipEventDisableTiming);
-      if (e != hipSuccess) return fail_hip(e, "pinned L2 ring");
-    }
-    c->l2_slot_bytes = slot_bytes;
-  }
+  rc = ensure_l2_ring(c, (size_t)job.chunk_blocks * c->blk_bytes, job.n_slots);
+  if (rc != CALVO_OK) return rc;
   const int64_t nck_l3 = job.chunk_ready ? (max_blocks + job.chunk_blocks - 1) / job.chunk_blocks : 0;
   for (int l = layer_begin; l < layer_end; l++)
     while ((int64_t)c->ev_chunk[l].size() < nck_l3) {         // the loader records them, this thread makes them
@@ -1075,16 +1047,26 @@ int calvo_layer_event(calvo_ctx* c, int layer, int mode, void* stream) {
   return CALVO_OK;
 }
 
-static hipError_t launch_attn(int variant, const AttnParams& p, hipStream_t stream) {
-  return variant == kAttnDuo ? launch_attn_duo(p, stream) : launch_attn_pipe(p, stream);
-}
+}  // extern "C"
 
-// use_static: descriptors and split-KV partial results go to this device's file-scope array and
-// nothing is allocated (calvo_prefill_attn_noalloc); otherwise to buffers the context grows on demand.
-static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
-                             const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale, bool use_static) {
-  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
-  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+namespace {
+
+// What one attention call launches for a batch: decided on the host from the batch's lengths (and, for
+// a layer loaded in chunks, from the chunk size), together with the descriptor words the kernels read.
+struct AttnPlan {
+  bool mfma = false;
+  int HW = 1, variant = 0, tile_tokens = 1;
+  int n_reqs = 0, total = 0;            // requests, suffix tokens over all of them
+  bool chunked = false;
+  int nck = 0;
+  PlanItems plan;
+  std::vector<int32_t> blob;
+  BlobLayout lay;
+  size_t part_need = 0;                 // split-KV partial-result slots the launch writes
+};
+
+// Argument checks of an attention call that do not depend on the layer.  *total = suffix tokens.
+int check_batch_args(const calvo_ctx* c, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, int* total) {
   std::vector<char> seen;
   int rc = validate_requests(c, reqs, n_reqs, false, seen);
   if (rc != CALVO_OK) return rc;
@@ -1093,7 +1075,11 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
   for (int r = 0; r < n_reqs; r++)
     if (cu_suffix[r + 1] - cu_suffix[r] != reqs[r].suffix_len)
       return fail(CALVO_EINVAL, "cu_suffix[%d+1]-cu_suffix[%d] != suffix_len of request %d", r, r, r);
-  const int total = n_reqs > 0 ? cu_suffix[n_reqs] : 0;
+  *total = n_reqs > 0 ? cu_suffix[n_reqs] : 0;
+  return CALVO_OK;
+}
+
+int check_pointer_args(const void* q, const void* k_suffix, const void* v_suffix, const void* out, int total) {
   if ((k_suffix == nullptr) != (v_suffix == nullptr))
     return fail(CALVO_EINVAL, "k_suffix and v_suffix must both be given or both be NULL");
   if (total > 0) {
@@ -1101,71 +1087,232 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
     if ((((uintptr_t)q | (uintptr_t)out | (uintptr_t)k_suffix | (uintptr_t)v_suffix) & 15) != 0)
       return fail(CALVO_EINVAL, "q, out, k_suffix and v_suffix must be 16-byte aligned");
   }
+  return CALVO_OK;
+}
+
+// cb > 0: the layer was loaded in nck chunks of cb block indices and attention follows the chunks.
+void make_attn_plan(calvo_ctx* c, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, int total, int cb,
+                    int nck, AttnPlan& ap) {
+  const calvo_config& cf = c->cfg;
+  ap.n_reqs = n_reqs;
+  ap.total = total;
+  ap.mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
+  ap.HW = attn_heads_per_wg(cf.n_q_heads, cf.n_kv_heads);
+  ap.variant = 0;
+  std::vector<int32_t> pblocks(n_reqs), slens(n_reqs);
+  for (int r = 0; r < n_reqs; r++) { pblocks[r] = reqs[r].n_prefix_blocks; slens[r] = reqs[r].suffix_len; }
+  if (ap.mfma) ap.variant = attn_mfma_choose(slens.data(), n_reqs, ap.HW);
+  ap.tile_tokens = ap.mfma ? attn_mfma_tile_tokens(ap.variant, ap.HW) : 1;
+  // Work items: tiles of suffix tokens, heaviest first, each possibly cut into split-KV pieces
+  // (consecutive work items) that the merge kernel combines; see attn_plan.cpp.
+  ap.chunked = ap.mfma && cb > 0 && !c->force_splits;
+  ap.nck = nck;
+  ap.plan = PlanItems();
+  if (ap.mfma) {
+    const std::vector<PlanTile> tiles = plan_tiles(pblocks.data(), slens.data(), n_reqs, ap.tile_tokens);
+    const PlanParams pp{cf.n_q_heads / ap.HW, c->n_cus * (8 / attn_mfma_waves_per_wg(ap.variant)), c->split_min, c->split_fill,
+                        c->force_splits};
+    if (ap.chunked) {
+      ap.plan = plan_items_chunked(tiles, pblocks.data(), cb, nck);
+    } else {
+      // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
+      // is kept for the following layers
+      std::vector<int64_t> key;
+      key.reserve(2 * n_reqs + 1);
+      key.push_back(ap.variant);
+      for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
+      int want = 1;
+      if (!c->force_splits && key == c->plan_key) want = c->plan_want;
+      else {
+        want = plan_pieces(tiles, pp);
+        if (!c->force_splits) { c->plan_key = key; c->plan_want = want; }
+      }
+      ap.plan = plan_items(tiles, want, pp);
+    }
+  }
+  ap.lay = build_descriptor_blob(c, reqs, n_reqs, cu_suffix, ap.plan, ap.blob);
+  ap.part_need = ap.plan.split_tiles.empty()
+                     ? 0
+                     : ap.plan.items.size() * (size_t)(cf.n_q_heads / ap.HW) * (size_t)attn_mfma_waves_per_wg(ap.variant);
+}
+
+hipError_t launch_attn(int variant, const AttnParams& p, hipStream_t stream) {
+  return variant == kAttnDuo ? launch_attn_duo(p, stream) : launch_attn_pipe(p, stream);
+}
+
+// Queues the suffix append and the attention of one layer on the compute stream.  d_att: the device
+// copy of ap.blob.  ready: NULL = the layer's own loading state decides what the stream waits for.
+int launch_layer(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out, float scale,
+                 const AttnPlan& ap, const int32_t* d_att, float* part_o, float* part_ml, hipEvent_t ready) {
+  const calvo_config& cf = c->cfg;
+  int rc;
+  if (ready) {
+    HIP_TRY(hipStreamWaitEvent(c->s_compute, ready, 0));   // the caller's own signal for this layer's blocks
+  } else if (!ap.chunked) {
+    rc = wait_handed_over(c, layer);        // a running L3 loader: until the layer's last chunk is queued
+    if (rc != CALVO_OK) return rc;
+    // chunk-granular launches wait for their own chunk; everything else for the whole layer.  The
+    // suffix rows go to slots no load writes, so they may be stored before the layer is in.
+    if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+  }
+  unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
+  const ReqDesc* d_reqs = (const ReqDesc*)d_att;
+  const int32_t* d_tables = d_att + ap.lay.tables_off;
+
+  if (k_suffix) {
+    AppendParams app{};
+    app.k_suffix = k_suffix; app.v_suffix = v_suffix; app.pool_layer = pool_layer;
+    app.reqs = d_reqs; app.tables = d_tables; app.n_reqs = ap.n_reqs; app.total_tokens = ap.total;
+    app.row_chunks = (int32_t)((size_t)cf.n_kv_heads * cf.head_dim * c->elt / 16);
+    HIP_TRY(launch_suffix_append(app, c->s_compute));
+  }
+
+  AttnParams p{};
+  p.q = q; p.out = out; p.pool_layer = pool_layer;
+  p.reqs = d_reqs; p.items = (const WorkItem*)(d_att + ap.lay.items_off); p.tables = d_tables;
+  p.blk_offs = (const int64_t*)(d_att + ap.lay.offs_off);
+  p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
+  p.heads_per_wg = ap.HW; p.tile_tokens = ap.tile_tokens;
+  p.waves_per_wg = attn_mfma_waves_per_wg(ap.variant);
+  p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
+  HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
+  if (ap.mfma) {
+    p.part_o = part_o;
+    p.part_ml = part_ml;
+    const auto& groups = ap.plan.groups;
+    if (ap.chunked) {
+      for (size_t g = 0; g < groups.size(); g++) {
+        // a device-side wait needs a recorded event: with a loader running, this thread follows it chunk by chunk
+        if (g < (size_t)ap.nck) {
+          if ((rc = wait_chunk_handed_over(c, layer, (int)g)) != CALVO_OK) return rc;
+          HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_chunk[layer][g], 0));
+        } else {
+          if ((rc = wait_handed_over(c, layer)) != CALVO_OK) return rc;
+          if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+        }
+        if (groups[g].empty()) continue;
+        p.n_items = (int32_t)groups[g].size();
+        p.item_index = d_att + ap.lay.group_off[g];
+        HIP_TRY(launch_attn(ap.variant, p, c->s_compute));
+      }
+      p.item_index = nullptr;
+    } else {
+      p.n_items = (int32_t)ap.plan.items.size();
+      HIP_TRY(launch_attn(ap.variant, p, c->s_compute));
+    }
+    HIP_TRY(launch_merge_splits(p, d_att + ap.lay.split_off, (int)ap.plan.split_tiles.size(), c->s_compute));
+  } else {
+    p.n_items = ap.n_reqs;
+    HIP_TRY(launch_attn_simple(p, cf.dtype, ap.total, c->s_compute));
+  }
+  HIP_TRY(hipEventRecord(c->ev_t1[layer], c->s_compute));
+  c->timed[layer] = 1;
+  c->last_variant[layer] = ap.mfma ? ap.variant : -1;
+  c->last_wgs[layer] = ap.mfma ? (int32_t)(ap.plan.items.size() * (size_t)(cf.n_q_heads / ap.HW)) : 0;
+  return CALVO_OK;
+}
+
+}  // namespace
+
+// A batch whose requests were validated, planned and described to the device once
+// (calvo_batch_prepare): the per-layer call then only queues its launches.
+struct PreparedPlan {
+  AttnPlan ap;
+  int32_t* d_blob = nullptr;                  // device copy of ap.blob (owned)
+  int32_t* h_blob = nullptr;                  // its pinned source (read when the compute stream gets to the upload)
+  size_t blob_bytes = 0;                      // capacity of both
+};
+
+struct calvo_batch {
+  calvo_ctx* c = nullptr;
+  std::vector<std::vector<int32_t>> tables;   // copies of the block tables
+  std::vector<calvo_request> reqs;            // block_table points into `tables`
+  std::vector<int32_t> cu;
+  PreparedPlan whole;                         // the launch for a layer loaded as a whole
+  // launches that follow a layer's chunks, made at the first such layer and kept: key = (chunk size in
+  // blocks, number of chunks)
+  std::vector<std::pair<std::pair<int, int>, PreparedPlan*>> chunked;
+};
+
+namespace {
+
+// device + pinned copies of pp.ap.blob, upload queued on the compute stream
+int upload_prepared(calvo_ctx* c, PreparedPlan& pp) {
+  const size_t bytes = std::max<size_t>(pp.ap.blob.size(), 4) * 4;
+  {
+    // the smallest buffer pair that was given back and is large enough
+    std::lock_guard<std::mutex> lk(c->blob_mu);
+    int best = -1;
+    for (int i = 0; i < (int)c->blob_free.size(); i++)
+      if (c->blob_free[i].bytes >= bytes && (best < 0 || c->blob_free[i].bytes < c->blob_free[best].bytes)) best = i;
+    if (best >= 0) {
+      pp.d_blob = c->blob_free[best].d; pp.h_blob = c->blob_free[best].h; pp.blob_bytes = c->blob_free[best].bytes;
+      c->blob_free.erase(c->blob_free.begin() + best);
+    }
+  }
+  if (!pp.d_blob) {
+    const size_t cap = (bytes + 65535) / 65536 * 65536;
+    HIP_TRY(hipMalloc((void**)&pp.d_blob, cap));
+    HIP_TRY(hipHostMalloc((void**)&pp.h_blob, cap, hipHostMallocDefault));
+    pp.blob_bytes = cap;
+  }
+  if (pp.ap.part_need) {
+    const int rc = ensure_partials(c, pp.ap.part_need);
+    if (rc != CALVO_OK) return rc;
+  }
+  memcpy(pp.h_blob, pp.ap.blob.data(), pp.ap.blob.size() * 4);
+  HIP_TRY(hipMemcpyAsync(pp.d_blob, pp.h_blob, pp.ap.blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+  return CALVO_OK;
+}
+
+// The launches that read the buffers have finished (or were never queued).
+void free_prepared(calvo_ctx* c, PreparedPlan& pp) {
+  constexpr size_t kKeep = 64;
+  bool kept = false;
+  if (c && pp.d_blob && pp.h_blob) {
+    std::lock_guard<std::mutex> lk(c->blob_mu);
+    if (c->blob_free.size() < kKeep) { c->blob_free.push_back({pp.d_blob, pp.h_blob, pp.blob_bytes}); kept = true; }
+  }
+  if (!kept) {
+    if (pp.d_blob) (void)hipFree(pp.d_blob);
+    if (pp.h_blob) (void)hipHostFree(pp.h_blob);
+  }
+  pp.d_blob = pp.h_blob = nullptr;
+  pp.blob_bytes = 0;
+}
+
+}  // namespace
+
+// use_static: descriptors and split-KV partial results go to this device's file-scope array and
+// nothing is allocated (calvo_prefill_attn_noalloc); otherwise to buffers the context grows on demand.
+int calvo::host::prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
+                                   const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale, bool use_static,
+                                   hipEvent_t ready) {
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  int total = 0;
+  int rc = check_batch_args(c, reqs, n_reqs, cu_suffix, &total);
+  if (rc != CALVO_OK) return rc;
+  rc = check_pointer_args(q, k_suffix, v_suffix, out, total);
+  if (rc != CALVO_OK) return rc;
   if (total == 0) {
     // nothing to compute; still order the compute stream after the layer's ingest
+    if (ready) { HIP_TRY(hipStreamWaitEvent(c->s_compute, ready, 0)); return CALVO_OK; }
     rc = wait_handed_over(c, layer);
     if (rc != CALVO_OK) return rc;
     if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
     return CALVO_OK;
   }
-
-  const calvo_config& cf = c->cfg;
-  const bool mfma = cf.dtype == CALVO_BF16 && cf.head_dim == 128;
-  const int HW = attn_heads_per_wg(cf.n_q_heads, cf.n_kv_heads);
-  int variant = 0;
-  if (mfma) {
-    std::vector<int32_t> slens(n_reqs);
-    for (int r = 0; r < n_reqs; r++) slens[r] = reqs[r].suffix_len;
-    variant = attn_mfma_choose(slens.data(), n_reqs, HW);
-  }
-  const int tile_tokens = mfma ? attn_mfma_tile_tokens(variant, HW) : 1;
-
-  // Work items: tiles of suffix tokens, heaviest first, each possibly cut into split-KV pieces
-  // (consecutive work items) that the merge kernel combines; see attn_plan.cpp.
-  PlanItems plan;
   int cb = 0, nck = 0;
-  {
+  if (!ready) {      // a layer loaded in chunks: attention follows the chunks, one launch behind each chunk's event
     std::lock_guard<std::mutex> lk(c->mu);
     cb = c->chunk_blocks[layer];
     nck = c->n_chunks[layer];
   }
-  // a layer loaded in chunks: attention follows the chunks, one launch behind each chunk's event
-  const bool chunked = mfma && cb > 0 && !c->force_splits;
-  if (mfma) {
-    std::vector<int32_t> pblocks(n_reqs), slens(n_reqs);
-    for (int r = 0; r < n_reqs; r++) { pblocks[r] = reqs[r].n_prefix_blocks; slens[r] = reqs[r].suffix_len; }
-    const std::vector<PlanTile> tiles = plan_tiles(pblocks.data(), slens.data(), n_reqs, tile_tokens);
-    const PlanParams pp{cf.n_q_heads / HW, c->n_cus * (8 / attn_mfma_waves_per_wg(variant)), c->split_min, c->split_fill,
-                        c->force_splits};
-    if (chunked) {
-      plan = plan_items_chunked(tiles, pblocks.data(), cb, nck);
-    } else {
-      int want = 1;
-      {
-        // the decision (a replay of the launch, attn_plan.cpp) depends only on the batch's lengths and
-        // is kept for the following layers
-        std::vector<int64_t> key;
-        key.reserve(2 * n_reqs + 1);
-        key.push_back(variant);
-        for (int r = 0; r < n_reqs; r++) { key.push_back(reqs[r].n_prefix_blocks); key.push_back(reqs[r].suffix_len); }
-        if (!c->force_splits && key == c->plan_key) want = c->plan_want;
-        else {
-          want = plan_pieces(tiles, pp);
-          if (!c->force_splits) { c->plan_key = key; c->plan_want = want; }
-        }
-      }
-      plan = plan_items(tiles, want, pp);
-    }
-  }
-  const std::vector<WorkItem>& items = plan.items;
-  const std::vector<int32_t>& split_tiles = plan.split_tiles;
-  const std::vector<std::vector<int32_t>>& groups = plan.groups;
-  std::vector<int32_t> blob;
-  const BlobLayout lay = build_descriptor_blob(c, reqs, n_reqs, cu_suffix, plan, blob);
-  const size_t items_off = lay.items_off, split_off = lay.split_off, tables_off = lay.tables_off, offs_off = lay.offs_off;
-  const std::vector<size_t>& group_off = lay.group_off;
+  AttnPlan ap;
+  make_attn_plan(c, reqs, n_reqs, cu_suffix, total, cb, nck, ap);
+  const std::vector<int32_t>& blob = ap.blob;
 
-  const size_t part_need = split_tiles.empty() ? 0 : items.size() * (size_t)(cf.n_q_heads / HW) * (size_t)attn_mfma_waves_per_wg(variant);
   int32_t* d_att = c->d_att;
   float *part_o = c->part_o, *part_ml = c->part_ml;
   if (use_static) {
@@ -1174,9 +1321,9 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
     if (blob.size() > kStaticBlobInts)
       return fail(CALVO_ENOMEM, "calvo_prefill_attn_noalloc: the batch needs %zu descriptor words, the static array holds %zu "
                   "(use calvo_prefill_attn)", blob.size(), kStaticBlobInts);
-    if (part_need > kStaticPartSlots)
+    if (ap.part_need > kStaticPartSlots)
       return fail(CALVO_ENOMEM, "calvo_prefill_attn_noalloc: the launch needs %zu partial-result slots, the static array holds %zu "
-                  "(use calvo_prefill_attn)", part_need, kStaticPartSlots);
+                  "(use calvo_prefill_attn)", ap.part_need, kStaticPartSlots);
     d_att = (int32_t*)c->d_static;
     part_o = (float*)(c->d_static + kStaticBlobBytes);
     part_ml = (float*)(c->d_static + kStaticBlobBytes + kStaticPartOBytes);
@@ -1190,99 +1337,132 @@ static int prefill_attn_impl(calvo_ctx* c, int layer, const void* q, const void*
   } else {
     rc = ensure_att_blob(c, blob.size());
     if (rc != CALVO_OK) return rc;
-    if (part_need) {
-      rc = ensure_partials(c, part_need);
+    if (ap.part_need) {
+      rc = ensure_partials(c, ap.part_need);
       if (rc != CALVO_OK) return rc;
     }
     d_att = c->d_att;
     part_o = c->part_o;
     part_ml = c->part_ml;
-  }
-  const bool same = use_static || (c->att_len == blob.size() && memcmp(c->h_att[c->att_cur], blob.data(), blob.size() * 4) == 0);
-  if (!same) {
-    const int k = (c->att_cur + 1) % calvo_ctx::kShadows;      // the shadow whose upload is the oldest
-    if (c->att_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_att[k])); c->att_pending[k] = false; }
-    c->att_len = 0;                       // the device copy is unknown until the transfer is queued
-    memcpy(c->h_att[k], blob.data(), blob.size() * 4);
-    HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att[k], blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
-    c->att_cur = k;
-    c->att_len = blob.size();
-    HIP_TRY(hipEventRecord(c->ev_att[k], c->s_compute));
-    c->att_pending[k] = true;
-  }
-
-  if (!chunked) {
-    rc = wait_handed_over(c, layer);        // a running L3 loader: until the layer's last chunk is queued
-    if (rc != CALVO_OK) return rc;
-  }
-  // chunk-granular launches wait for their own chunk; everything else for the whole layer.  The
-  // suffix rows go to slots no load writes, so they may be stored before the layer is in.
-  if (!chunked && layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
-
-  unsigned char* pool_layer = (unsigned char*)cf.pool + (int64_t)layer * c->layer_bytes;
-  const ReqDesc* d_reqs = (const ReqDesc*)d_att;
-  const int32_t* d_tables = d_att + tables_off;
-
-  if (k_suffix) {
-    AppendParams ap{};
-    ap.k_suffix = k_suffix; ap.v_suffix = v_suffix; ap.pool_layer = pool_layer;
-    ap.reqs = d_reqs; ap.tables = d_tables; ap.n_reqs = n_reqs; ap.total_tokens = total;
-    ap.row_chunks = (int32_t)((size_t)cf.n_kv_heads * cf.head_dim * c->elt / 16);
-    HIP_TRY(launch_suffix_append(ap, c->s_compute));
-  }
-
-  AttnParams p{};
-  p.q = q; p.out = out; p.pool_layer = pool_layer;
-  p.reqs = d_reqs; p.items = (const WorkItem*)(d_att + items_off); p.tables = d_tables;
-  p.blk_offs = (const int64_t*)(d_att + offs_off);
-  p.n_q_heads = cf.n_q_heads; p.n_kv_heads = cf.n_kv_heads; p.head_dim = cf.head_dim;
-  p.heads_per_wg = HW; p.tile_tokens = tile_tokens;
-  p.waves_per_wg = attn_mfma_waves_per_wg(variant);
-  p.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)cf.head_dim);
-  HIP_TRY(hipEventRecord(c->ev_t0[layer], c->s_compute));
-  if (mfma) {
-    p.part_o = part_o;
-    p.part_ml = part_ml;
-    if (chunked) {
-      for (size_t g = 0; g < groups.size(); g++) {
-        // a device-side wait needs a recorded event: with a loader running, this thread follows it chunk by chunk
-        if (g < (size_t)nck) {
-          if ((rc = wait_chunk_handed_over(c, layer, (int)g)) != CALVO_OK) return rc;
-          HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_chunk[layer][g], 0));
-        } else {
-          if ((rc = wait_handed_over(c, layer)) != CALVO_OK) return rc;
-          if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
-        }
-        if (groups[g].empty()) continue;
-        p.n_items = (int32_t)groups[g].size();
-        p.item_index = d_att + group_off[g];
-        HIP_TRY(launch_attn(variant, p, c->s_compute));
-      }
-      p.item_index = nullptr;
-    } else {
-      p.n_items = (int32_t)items.size();
-      HIP_TRY(launch_attn(variant, p, c->s_compute));
+    const bool same = c->att_len == blob.size() && memcmp(c->h_att[c->att_cur], blob.data(), blob.size() * 4) == 0;
+    if (!same) {
+      const int k = (c->att_cur + 1) % calvo_ctx::kShadows;      // the shadow whose upload is the oldest
+      if (c->att_pending[k]) { HIP_TRY(hipEventSynchronize(c->ev_att[k])); c->att_pending[k] = false; }
+      c->att_len = 0;                       // the device copy is unknown until the transfer is queued
+      memcpy(c->h_att[k], blob.data(), blob.size() * 4);
+      HIP_TRY(hipMemcpyAsync(c->d_att, c->h_att[k], blob.size() * 4, hipMemcpyHostToDevice, c->s_compute));
+      c->att_cur = k;
+      c->att_len = blob.size();
+      HIP_TRY(hipEventRecord(c->ev_att[k], c->s_compute));
+      c->att_pending[k] = true;
     }
-    HIP_TRY(launch_merge_splits(p, d_att + split_off, (int)split_tiles.size(), c->s_compute));
-  } else {
-    p.n_items = n_reqs;
-    HIP_TRY(launch_attn_simple(p, cf.dtype, total, c->s_compute));
   }
-  HIP_TRY(hipEventRecord(c->ev_t1[layer], c->s_compute));
-  c->timed[layer] = 1;
-  c->last_variant[layer] = mfma ? variant : -1;
-  c->last_wgs[layer] = mfma ? (int32_t)(items.size() * (size_t)(cf.n_q_heads / HW)) : 0;
+  return launch_layer(c, layer, q, k_suffix, v_suffix, out, scale, ap, d_att, part_o, part_ml, ready);
+}
+
+int calvo::host::prefill_attn_prepared(calvo_batch* b, int layer, const void* q, const void* k_suffix, const void* v_suffix,
+                                       void* out, float scale, hipEvent_t ready) {
+  if (!b || !b->c) return fail(CALVO_EINVAL, "batch is NULL");
+  calvo_ctx* c = b->c;
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(CALVO_EINVAL, "layer %d outside [0, %d)", layer, c->cfg.n_layers);
+  int rc = check_pointer_args(q, k_suffix, v_suffix, out, b->whole.ap.total);
+  if (rc != CALVO_OK) return rc;
+  PreparedPlan* pp = &b->whole;
+  if (!ready && b->whole.ap.total > 0) {
+    // a layer that was loaded in chunks gets the launches that follow its chunks: planned and
+    // uploaded the first time that chunking is seen, kept for the other layers and steps
+    int cb = 0, nck = 0;
+    {
+      std::lock_guard<std::mutex> lk(c->mu);
+      cb = c->chunk_blocks[layer];
+      nck = c->n_chunks[layer];
+    }
+    if (cb > 0 && b->whole.ap.mfma && !c->force_splits) {
+      pp = nullptr;
+      for (auto& e : b->chunked)
+        if (e.first == std::make_pair(cb, nck)) pp = e.second;
+      if (!pp) {
+        pp = new (std::nothrow) PreparedPlan();
+        if (!pp) return fail(CALVO_ENOMEM, "out of host memory");
+        make_attn_plan(c, b->reqs.data(), (int)b->reqs.size(), b->cu.data(), b->whole.ap.total, cb, nck, pp->ap);
+        rc = upload_prepared(c, *pp);
+        if (rc != CALVO_OK) { free_prepared(c, *pp); delete pp; return rc; }
+        b->chunked.push_back({{cb, nck}, pp});
+      }
+    }
+  }
+  if (b->whole.ap.total == 0) {
+    if (ready) { HIP_TRY(hipStreamWaitEvent(c->s_compute, ready, 0)); return CALVO_OK; }
+    rc = wait_handed_over(c, layer);
+    if (rc != CALVO_OK) return rc;
+    if (layer_is_issued(c, layer)) HIP_TRY(hipStreamWaitEvent(c->s_compute, c->ev_layer[layer], 0));
+    return CALVO_OK;
+  }
+  return launch_layer(c, layer, q, k_suffix, v_suffix, out, scale, pp->ap, pp->d_blob, c->part_o, c->part_ml, ready);
+}
+
+void calvo::host::batch_free_completed(calvo_batch* b) {
+  if (!b) return;
+  free_prepared(b->c, b->whole);
+  for (auto& e2 : b->chunked) { free_prepared(b->c, *e2.second); delete e2.second; }
+  delete b;
+}
+
+extern "C" {
+
+int calvo_batch_prepare(calvo_ctx* c, const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, calvo_batch** out) {
+  if (!out) return fail(CALVO_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!c) return fail(CALVO_EINVAL, "ctx is NULL");
+  int total = 0;
+  int rc = check_batch_args(c, reqs, n_reqs, cu_suffix, &total);
+  if (rc != CALVO_OK) return rc;
+  calvo_batch* b = new (std::nothrow) calvo_batch();
+  if (!b) return fail(CALVO_ENOMEM, "out of host memory");
+  b->c = c;
+  b->tables.resize((size_t)n_reqs);
+  b->reqs.assign(reqs, reqs + n_reqs);
+  for (int r = 0; r < n_reqs; r++) {
+    const int64_t nt = (int64_t)reqs[r].n_prefix_blocks + (reqs[r].suffix_len + kBlockTokens - 1) / kBlockTokens;
+    b->tables[r].assign(reqs[r].block_table, reqs[r].block_table + nt);
+    b->reqs[r].block_table = b->tables[r].data();
+  }
+  b->cu.assign(cu_suffix, cu_suffix + (n_reqs > 0 ? n_reqs + 1 : 0));
+  if (n_reqs == 0) b->cu.assign(1, 0);
+  make_attn_plan(c, b->reqs.data(), n_reqs, b->cu.data(), total, 0, 0, b->whole.ap);
+  rc = upload_prepared(c, b->whole);
+  if (rc != CALVO_OK) {
+    const std::string msg = calvo_last_error();
+    (void)calvo_batch_destroy(b);
+    return fail(rc, "%s", msg.c_str());
+  }
+  *out = b;
   return CALVO_OK;
+}
+
+int calvo_batch_destroy(calvo_batch* b) {
+  if (!b) return fail(CALVO_EINVAL, "batch is NULL");
+  hipError_t e = hipSuccess;
+  if (b->c && b->c->s_compute) e = hipStreamSynchronize(b->c->s_compute);   // launches that read its descriptors
+  batch_free_completed(b);
+  if (e != hipSuccess) return fail_hip(e, "synchronize at calvo_batch_destroy");
+  return CALVO_OK;
+}
+
+int calvo_prefill_attn_batch(calvo_ctx* c, calvo_batch* b, int layer, const void* q, const void* k_suffix, const void* v_suffix,
+                             void* out, float scale) {
+  if (!c || !b || b->c != c) return fail(CALVO_EINVAL, "batch does not belong to this context");
+  return prefill_attn_prepared(b, layer, q, k_suffix, v_suffix, out, scale, nullptr);
 }
 
 int calvo_prefill_attn(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
                        const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
-  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, false);
+  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, false, nullptr);
 }
 
 int calvo_prefill_attn_noalloc(calvo_ctx* c, int layer, const void* q, const void* k_suffix, const void* v_suffix, void* out,
                                const calvo_request* reqs, int n_reqs, const int32_t* cu_suffix, float scale) {
-  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, true);
+  return prefill_attn_impl(c, layer, q, k_suffix, v_suffix, out, reqs, n_reqs, cu_suffix, scale, true, nullptr);
 }
 
 int calvo_attn_kernel_info(calvo_ctx* c, int layer, int* kernel, int* n_workgroups) {

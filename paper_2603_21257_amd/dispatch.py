@@ -1,7 +1,10 @@
-"""Multi-request dispatcher on top of the C ABI (paper Section 3.2): whenever the GPU path is
-free, the library's scheduler (calvo_sched_pick) chooses among the requests that have arrived,
-and the chosen request is run to its first token.  Sequencing and time keeping only - the
-policy arithmetic is in the library, the work in its HIP code.
+"""Callers of the library's multi-request dispatcher (paper Sections 3.1 and 3.2).
+
+The stage threads, the queues, the policy order, the slot admission and the hand-over between the
+stages are inside libcalvo (calvo_dispatch_*); this module only keeps time for a trace: it submits
+every request at its arrival time and collects the results.  serve_trace_serial is the baseline the
+paper's dispatcher is compared with: one request at a time, the library's scheduler choosing the
+next one.
 """
 from __future__ import annotations
 
@@ -11,10 +14,96 @@ from typing import Callable, Optional, Sequence
 from . import binding as cb
 
 
-def serve_trace(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
-                run_request: Callable[[int], None], clock: Callable[[], float] = time.perf_counter,
+class Dispatcher:
+    """Handle of a calvo_dispatcher: `with Dispatcher(ctx, policy, ...) as d: d.submit(...); d.wait(i)`."""
+
+    def __init__(self, ctx: Optional[int], policy: int, model=None, **kw):
+        self.handle = cb.calvo_dispatch_create(ctx, policy, model, **kw)
+
+    def submit(self, **job) -> int:
+        return cb.calvo_dispatch_submit(self.handle, **job)
+
+    def wait(self, job: int) -> dict:
+        return cb.calvo_dispatch_wait(self.handle, job)
+
+    def poll(self, job: int):
+        return cb.calvo_dispatch_poll(self.handle, job)
+
+    def table(self, job: int):
+        return cb.calvo_dispatch_table(self.handle, job)
+
+    def release(self, job: int) -> None:
+        cb.calvo_dispatch_release(self.handle, job)
+
+    def stats(self) -> dict:
+        return cb.calvo_dispatch_stats_get(self.handle)
+
+    def close(self) -> None:
+        if self.handle:
+            h, self.handle = self.handle, 0
+            cb.calvo_dispatch_destroy(h)
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+        return False
+
+
+def serve_trace(d: Dispatcher, arrivals: Sequence[float], make_job: Callable[[int], dict], hold_s: Optional[Sequence[float]] = None,
+                on_finish: Optional[Callable[[int, int, dict], None]] = None, clock: Callable[[], float] = time.perf_counter,
                 sleep: Callable[[float], None] = time.sleep):
-    """Serves every job once, non-preemptively, in the order the policy dictates.
+    """Submits request i (keyword arguments of calvo_dispatch_submit from make_job(i)) at arrivals[i]
+    seconds after entry, in the order of arrivals, and returns the list of results
+    (calvo_dispatch_result as dicts, times on the dispatcher's clock) indexed like arrivals.
+
+    hold_s[i]: request i keeps its HBM slots this long after its first token (the decode phase that
+    follows the prefill), then they are released; None releases at the first token.  on_finish(i,
+    job id, result) runs when request i has finished, before its slots are released.
+    """
+    n = len(arrivals)
+    order = sorted(range(n), key=lambda i: (arrivals[i], i))
+    ids, results = [None] * n, [None] * n
+    holders = []                                            # (release time, request)
+    pending = []
+    t0 = clock()
+
+    def collect():
+        # polls: a request that waits for HBM slots only moves on when a finished one is released here
+        for i in list(pending):
+            res = d.poll(ids[i])
+            if res is None:
+                continue
+            pending.remove(i)
+            results[i] = res
+            if on_finish:
+                on_finish(i, ids[i], res)
+            holders.append((clock() - t0 + (float(hold_s[i]) if hold_s is not None else 0.0), i))
+        now = clock() - t0
+        for when, i in [h for h in holders if h[0] <= now]:
+            d.release(ids[i])
+            holders.remove((when, i))
+
+    for i in order:
+        while True:
+            now = clock() - t0
+            if now >= arrivals[i]:
+                break
+            collect()
+            sleep(min(arrivals[i] - now, 2e-4))
+        ids[i] = d.submit(**make_job(i))
+        pending.append(i)
+    while pending or holders:
+        collect()
+        sleep(2e-4)
+    return results
+
+
+def serve_trace_serial(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
+                       run_request: Callable[[int], None], clock: Callable[[], float] = time.perf_counter,
+                       sleep: Callable[[float], None] = time.sleep):
+    """One request at a time, non-preemptively, in the order the library's scheduler dictates.
 
     jobs[i] = (arrival_s, deadline_s, ctx_tokens, query_tokens), arrival relative to the moment this
     function is entered.  run_request(i) must return when request i's first token is ready.
@@ -35,108 +124,4 @@ def serve_trace(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Se
         run_request(i)
         finish[i] = clock() - t0
         done[i] = True
-    return start, finish
-
-
-def serve_trace_pooled(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
-                       pool: int, n_blocks: Sequence[int], run_request: Callable[[int, "object"], None],
-                       hold_s: Sequence[float], clock: Callable[[], float] = time.perf_counter,
-                       sleep: Callable[[float], None] = time.sleep):
-    """serve_trace with the KV slots of every request taken from a calvo_pool (paper Section 3.1,
-    proactive allocation): the moment a request is picked - when its loading is issued - its
-    n_blocks[i] destination slots are requested.  If HBM has room they are granted at once; if not,
-    the request waits for slots to come back (reactive allocation) and loading starts then.  Request
-    i keeps its slots for hold_s[i] seconds after its first token (the decode phase that follows the
-    prefill) and releases them afterwards.
-
-    run_request(i, table) gets the granted slot ids (int32 array of n_blocks[i]).
-    Returns (start_s, finish_s, reactive, alloc_wait_s): reactive[i] tells whether request i had to
-    wait for slots, alloc_wait_s[i] for how long.
-    """
-    n = len(jobs)
-    done = [False] * n
-    start, finish = [0.0] * n, [0.0] * n
-    reactive, alloc_wait = [False] * n, [0.0] * n
-    holders = []                                       # (release time, table)
-    t0 = clock()
-
-    def release_expired(now):
-        for when, table in holders:
-            if when <= now:
-                cb.calvo_pool_release(pool, table)
-        holders[:] = [h for h in holders if h[0] > now]
-
-    for _ in range(n):
-        while True:
-            now = clock() - t0
-            release_expired(now)
-            i = cb.calvo_sched_pick(policy, model, jobs, done, now)
-            if i >= 0:
-                break
-            sleep(max(0.0, min(jobs[k][0] for k in range(n) if not done[k]) - now))
-        table, ticket = cb.calvo_pool_admit(pool, [], int(n_blocks[i]))
-        if table is None:                              # HBM short: reactive allocation
-            reactive[i] = True
-            while table is None:
-                if not holders:
-                    cb.calvo_pool_cancel(pool, ticket)
-                    raise RuntimeError(f"request {i} needs {n_blocks[i]} slots and nothing is left to release")
-                wake = min(h[0] for h in holders)
-                sleep(max(0.0, wake - (clock() - t0)))
-                release_expired(clock() - t0)
-                table = cb.calvo_pool_retry(pool, ticket, int(n_blocks[i]))
-            alloc_wait[i] = (clock() - t0) - now
-        start[i] = clock() - t0
-        run_request(i, table)
-        finish[i] = clock() - t0
-        done[i] = True
-        holders.append((finish[i] + float(hold_s[i]), table))
-    for _, table in holders:
-        cb.calvo_pool_release(pool, table)
-    return start, finish, reactive, alloc_wait
-
-
-def serve_trace_two_stage(policy: int, model: Optional[Sequence[float]], jobs: Sequence[Sequence[float]],
-                          try_issue: Callable[[int], bool], load_done: Callable[[int], bool],
-                          finished: Callable[[int], bool], clock: Callable[[], float] = time.perf_counter,
-                          sleep: Callable[[float], None] = time.sleep, poll_s: float = 1e-4):
-    """Loading and computation as two stages that progress on their own (paper Section 3.1): the loading
-    stage takes the next request - the policy's pick among those that have arrived - as soon as the
-    previous request's blocks are all loaded, while that request (and earlier ones) may still be
-    computing; computation follows in the order of loading.
-
-    try_issue(i) queues request i's loading and computation without waiting for either and returns
-    True, or returns False if it cannot be queued yet (no room for its blocks: it is tried again);
-    load_done(i) tells whether all of i's blocks are loaded; finished(i) whether its first token is
-    ready.  Returns (start_s, finish_s) as serve_trace does; a finish time is taken when the loop
-    notices it (every poll_s while it idles).
-    """
-    n = len(jobs)
-    issued = [False] * n
-    start, finish = [0.0] * n, [0.0] * n
-    in_flight = []
-    loading = -1
-    n_done = 0
-    t0 = clock()
-    while n_done < n:
-        now = clock() - t0
-        for i in list(in_flight):
-            if finished(i):
-                finish[i] = now
-                in_flight.remove(i)
-                n_done += 1
-        if loading >= 0 and load_done(loading):
-            loading = -1
-        if loading < 0 and not all(issued):
-            i = cb.calvo_sched_pick(policy, model, jobs, issued, now)
-            if i >= 0 and try_issue(i):
-                start[i] = now
-                issued[i] = True
-                loading = i
-                in_flight.append(i)
-                continue
-            if i < 0 and not in_flight:
-                sleep(max(0.0, min(jobs[k][0] for k in range(n) if not issued[k]) - now))
-                continue
-        sleep(poll_s)
     return start, finish

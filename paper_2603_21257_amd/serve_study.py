@@ -1,6 +1,6 @@
 """The paper's scheduling comparison (Section 4.3) served for real on one GPU: a seeded trace of
-prefix-hit requests with Poisson arrivals goes through the dispatcher loop (dispatch.serve_trace)
-under each queue policy, every request running the whole HIP path - load its cached context from
+prefix-hit requests with Poisson arrivals is served one request at a time (dispatch.serve_trace_serial)
+or through the library's staged dispatcher (--two-stage, --three-stage) under each queue policy, every request running the whole HIP path - load its cached context from
 pinned host memory, prefill its query tokens layer by layer - and TTFTs are taken with the wall clock.
 The binary linear cost model is fitted from a few profiled requests first (Section 3.2: offline
 profiling), deadlines are the model's interference-free TTFT times 2, 4 or 8, and the library's own
@@ -13,7 +13,7 @@ lengths between 16 and 512 tokens, every context fully reusable; the stack is Ll
 read the same host bytes and reuse the same pool slots one after the other - service is
 non-preemptive and one request at a time, so nothing is shared in time.
 
-    python -m paper_2603_21257_amd.serve_study [--requests 48] [--load 1.2] [--seed 1]
+    python -m paper_2603_21257_amd.serve_study [--requests 48] [--load 1.2] [--seed 1] [--two-stage | --three-stage]
 """
 from __future__ import annotations
 
@@ -117,85 +117,102 @@ class Server:
         return (la, lb, ca, cbb)
 
 
-class PipelinedServer(Server):
-    """The same path with several requests in flight: a request's blocks get slots of their own from
-    the slot allocator (paper Section 3.1, allocation at the moment loading is issued), loading and
-    attention are queued without waiting, and the next request's loading starts while this one still
-    computes.  The compute stream is the caller's, so a request's completion can be polled."""
+class DispatchServer(Server):
+    """The same path behind the library's dispatcher (calvo_dispatch_*): loading and computation - and,
+    with three_stage, the emulated link below them - are stages of their own that work on different
+    requests at the same time (paper Section 3.1).  A request's blocks get slots from the slot
+    allocator when its lowest transfer is issued; the pool holds `depth` requests of the largest
+    size, so under load some requests find HBM short and are allocated reactively.
 
-    def __init__(self, n_layers=8, seed=7, max_query=MAX_QRY, depth=4):
+    pageable: the cached contexts sit in ordinary host memory (the remote store of the three-stage
+    path) instead of page-locked memory."""
+
+    def __init__(self, n_layers=8, seed=7, max_query=MAX_QRY, depth=4, pageable=False, l3_GBps=0.0):
         import torch
         self.torch = torch
         self.L, self.Hq, self.Hkv, self.D = n_layers, 32, 8, 128
-        self.max_query = max_query
+        self.max_query, self.pageable, self.l3_GBps = max_query, pageable, l3_GBps
         per_req = (MAX_CTX + max_query) // 16 + 1
         slots = depth * per_req
         self.shape = s = wl.Shape(self.L, self.Hq, self.Hkv, self.D, "bf16", slots)
         dev = torch.device("cuda:0")
         self.host_blocks = MAX_CTX // 16
-        self.arena = hostmem.PinnedBuffer(self.L * self.host_blocks * s.blk_bytes)
-        self.host = wl.fill_normal_(self.arena.tensor((self.L, self.host_blocks, s.blk_elems), torch.bfloat16), seed)
+        if pageable:
+            self.arena = None
+            self.host = wl.fill_normal_(torch.empty((self.L, self.host_blocks, s.blk_elems), dtype=torch.bfloat16), seed)
+        else:
+            self.arena = hostmem.PinnedBuffer(self.L * self.host_blocks * s.blk_bytes)
+            self.host = wl.fill_normal_(self.arena.tensor((self.L, self.host_blocks, s.blk_elems), torch.bfloat16), seed)
         self.pool = torch.empty((self.L, slots, s.blk_elems), dtype=torch.bfloat16, device=dev)
         mk = lambda h, sd: wl.fill_normal_(torch.empty((self.L, max_query, h, self.D), dtype=torch.bfloat16, device=dev), sd)
         self.q, self.ks, self.vs = mk(self.Hq, seed + 1), mk(self.Hkv, seed + 2), mk(self.Hkv, seed + 3)
-        self.outs = [torch.empty((self.L, max_query, self.Hq, self.D), dtype=torch.bfloat16, device=dev) for _ in range(depth)]
-        self.out = self.outs[0]
-        self.table = np.arange(per_req, dtype=np.int32)          # Server's single-request calls (profiling) use the first region
-        self.stream = torch.cuda.Stream()
-        self.ctx = cb.calvo_create(self.L, self.Hq, self.Hkv, self.D, cb.CALVO_BF16, slots, self.pool,
-                                   staging_bytes=256 << 20, compute_stream=self.stream.cuda_stream)
+        self.out = torch.empty((self.L, max_query, self.Hq, self.D), dtype=torch.bfloat16, device=dev)
+        self.table = np.arange(per_req, dtype=np.int32)          # the one-request-at-a-time calls use the first region
+        self.ctx = cb.calvo_create(self.L, self.Hq, self.Hkv, self.D, cb.CALVO_BF16, slots, self.pool, staging_bytes=256 << 20)
         self.slots = cb.calvo_pool_create(slots)
-        self.flight = {}                                         # request -> (table, done event, out index)
-        self.free_outs = list(range(depth))
-        self.last_issued = -1
 
     def close(self):
         if self.slots:
             cb.calvo_pool_destroy(self.slots)
             self.slots = 0
-        super().close()
+        if self.ctx:
+            cb.calvo_destroy(self.ctx)
+            self.ctx = 0
+        if self.arena:
+            self.arena.free()
 
-    def try_issue(self, i, ctx_tokens, qry_tokens):
-        nb = ctx_tokens // 16 + -(-qry_tokens // 16)
-        if not self.free_outs or cb.calvo_pool_counts(self.slots)["free"] < nb:
-            return False
-        table = cb.calvo_pool_reserve(self.slots, nb)
-        o = self.free_outs.pop()
-        stride = self.host_blocks * self.shape.blk_bytes
-        r = cb.make_request(self.host.data_ptr(), stride, table, ctx_tokens // 16, qry_tokens)
-        cu = np.array([0, qry_tokens], np.int32)
-        cb.calvo_kv_ingest(self.ctx, [r], 0, self.L)
-        out = self.outs[o]
-        for l in range(self.L):
-            cb.calvo_prefill_attn(self.ctx, l, self.q[l, :qry_tokens], self.ks[l, :qry_tokens], self.vs[l, :qry_tokens],
-                                  out[l, :qry_tokens], [r], cu, 0.0)
-        ev = self.torch.cuda.Event()
-        ev.record(self.stream)
-        self.flight[i] = (table, ev, o)
-        self.last_issued = i
-        return True
+    def _ingest(self, r):
+        if self.pageable:
+            cb.calvo_kv_ingest_l3(self.ctx, [r], 0, self.L, l3_GBps=self.l3_GBps)
+        else:
+            cb.calvo_kv_ingest(self.ctx, [r], 0, self.L)
 
-    def load_done(self, i):
-        # only asked about the request issued last: the per-layer events belong to the latest loading call
-        assert i == self.last_issued
-        return cb.calvo_layer_event(self.ctx, self.L - 1, cb.CALVO_EV_QUERY)
-
-    def finished(self, i):
-        table, ev, o = self.flight[i]
-        if not ev.query():
-            return False
-        cb.calvo_pool_release(self.slots, table)
-        self.free_outs.append(o)
-        del self.flight[i]
-        return True
-
-    def compute_only(self, ctx_tokens, qry_tokens):
-        super().compute_only(ctx_tokens, qry_tokens)
-        self.stream.synchronize()
+    def load_only(self, ctx_tokens, qry_tokens):
+        self._ingest(self.request(ctx_tokens, qry_tokens))
+        if self.pageable:
+            cb.calvo_l3_wait(self.ctx)
+        cb.calvo_layer_event(self.ctx, self.L - 1, cb.CALVO_EV_HOST_WAIT)
 
     def serve(self, ctx_tokens, qry_tokens):
-        super().serve(ctx_tokens, qry_tokens)
-        self.stream.synchronize()
+        r = self.request(ctx_tokens, qry_tokens)
+        cu = np.array([0, qry_tokens], np.int32)
+        self._ingest(r)
+        for l in range(self.L):
+            cb.calvo_prefill_attn(self.ctx, l, self.q[l, :qry_tokens], self.ks[l, :qry_tokens], self.vs[l, :qry_tokens],
+                                  self.out[l, :qry_tokens], [r], cu, 0.0)
+        if self.pageable:
+            cb.calvo_l3_wait(self.ctx)
+        self.torch.cuda.synchronize()
+
+    def run_trace(self, policy, model, jobs, three_stage=False, on_result=None):
+        """The trace through a dispatcher of its own; returns the list of calvo_dispatch_result dicts.
+        on_result(i, table, out) sees request i's granted table and its output [L][query][Hq][D] before
+        its slots are released."""
+        torch = self.torch
+        outs = {}
+        stride = self.host_blocks * self.shape.blk_bytes
+        q_stride = self.max_query * self.Hq * self.D * 2
+        kv_stride = self.max_query * self.Hkv * self.D * 2
+
+        with dispatch.Dispatcher(self.ctx, policy, model, three_stage=three_stage, pool=self.slots,
+                                 l3_GBps=self.l3_GBps if three_stage else 0.0) as d:
+            def make_job(i):
+                _, ddl, c, qn = jobs[i]
+                outs[i] = torch.empty((self.L, qn, self.Hq, self.D), dtype=torch.bfloat16, device=self.pool.device)
+                return dict(host_kv=self.host.data_ptr(), host_layer_stride=stride, n_prefix_blocks=c // 16, suffix_len=qn,
+                            q=self.q, k_suffix=self.ks, v_suffix=self.vs, out=outs[i], q_layer_stride=q_stride,
+                            kv_layer_stride=kv_stride, deadline_s=(ddl - jobs[i][0]) if math.isfinite(ddl) else 0.0)
+
+            def on_finish(i, jid, res):
+                if on_result:
+                    on_result(i, d.table(jid), outs[i])
+                outs.pop(i)                                   # the output buffer was this request's own
+
+            res = dispatch.serve_trace(d, [j[0] for j in jobs], make_job, on_finish=on_finish)
+            self.last_stats = d.stats()
+        counts = cb.calvo_pool_counts(self.slots)
+        assert counts["used"] == 0 and counts["waiting"] == 0, "slots left allocated after the trace"
+        return res
 
 
 def make_jobs(lengths, model, load, seed):
@@ -224,7 +241,7 @@ def study(n_requests=48, load=1.2, seed=1, n_layers=8, log=print):
         ddl = np.array([j[1] for j in jobs])
         res = {}
         for name, pol in POLICIES:
-            _, fin = dispatch.serve_trace(pol, model, jobs, lambda i: srv.serve(jobs[i][2], jobs[i][3]))
+            _, fin = dispatch.serve_trace_serial(pol, model, jobs, lambda i: srv.serve(jobs[i][2], jobs[i][3]))
             fin = np.array(fin)
             _, sim = cb.calvo_sched_simulate(pol, model, jobs, pipelined=0)
             res[name] = {"ttft_s": float(np.mean(fin - arr)), "replay_ttft_s": float(np.mean(sim - arr)),
@@ -234,11 +251,17 @@ def study(n_requests=48, load=1.2, seed=1, n_layers=8, log=print):
         srv.close()
 
 
-def study_two_stage(n_requests=48, load=1.2, seed=1, n_layers=8, max_query=MAX_QRY, policies=POLICIES, log=print):
-    """The same trace on the pipelined server, once request by request (serve_trace) and once with
-    loading and computation as two stages (serve_trace_two_stage).
-    {policy: dict(serial mean TTFT s, two-stage mean TTFT s, deadlines met by each)} and the model."""
-    srv = PipelinedServer(n_layers, max_query=max_query)
+def study_staged(n_requests=48, load=1.2, seed=1, n_layers=8, max_query=MAX_QRY, policies=POLICIES, three_stage=False,
+                 l3_GBps=50.0, depth=4, on_result=None, log=print):
+    """The same trace once request by request (serve_trace_serial) and once through the library's
+    dispatcher with its stages working on different requests at the same time: loading and computation
+    (two stages, contexts in page-locked memory), or - three_stage - the emulated link of l3_GBps in
+    front of them (contexts in pageable memory; the paper's Section 4.1 link is 400 Gbps = 50 GB/s).
+    {policy: dict(serial / staged mean TTFT s, deadlines met, spans, requests allocated reactively,
+    link utilisation)} and the model.  on_result(i, (ctx tokens, query tokens), table, out, server) sees
+    the granted block table and the output of every request of the untimed first pass (six requests
+    queued at once) before its slots are released."""
+    srv = DispatchServer(n_layers, max_query=max_query, depth=depth, pageable=three_stage, l3_GBps=l3_GBps if three_stage else 0.0)
     try:
         model = srv.fit_model()
         log(f"fitted cost model: load {model[0] * 1e6:.3f} us/token + {model[1] * 1e3:.3f} ms, "
@@ -249,20 +272,23 @@ def study_two_stage(n_requests=48, load=1.2, seed=1, n_layers=8, max_query=MAX_Q
         arr = np.array([j[0] for j in jobs])
         ddl = np.array([j[1] for j in jobs])
         res = {}
-        warm = [(0.0, math.inf, c, q) for c, q in lengths[:4]]           # first use of the two-stage path: untimed
-        dispatch.serve_trace_two_stage(cb.CALVO_POLICY_FIFO, model, warm, lambda i: srv.try_issue(i, warm[i][2], warm[i][3]),
-                                       srv.load_done, srv.finished, poll_s=0.0)
+        # first use of the staged path, untimed: the first requests of the trace, all queued at once; this
+        # is the pass whose results on_result sees (a check there would hold up the timed passes)
+        warm = [(0.0, math.inf, c, q) for c, q in lengths[:6]]
+        srv.run_trace(cb.CALVO_POLICY_FIFO, model, warm, three_stage,
+                      on_result=(lambda i, table, o: on_result(i, warm[i][2:], table, o, srv)) if on_result else None)
         for name, pol in policies:
-            _, fin1 = dispatch.serve_trace(pol, model, jobs, lambda i: srv.serve(jobs[i][2], jobs[i][3]))
-            # poll_s = 0: the loop spins (yielding the processor) so that a finished loading is noticed at once
-            _, fin2 = dispatch.serve_trace_two_stage(pol, model, jobs, lambda i: srv.try_issue(i, jobs[i][2], jobs[i][3]),
-                                                     srv.load_done, srv.finished, poll_s=0.0)
-            fin1, fin2 = np.array(fin1), np.array(fin2)
-            res[name] = {"serial_ttft_s": float(np.mean(fin1 - arr)), "two_stage_ttft_s": float(np.mean(fin2 - arr)),
-                         "serial_met": float(np.mean(fin1 <= ddl)), "two_stage_met": float(np.mean(fin2 <= ddl)),
-                         "serial_span_s": float(fin1.max()), "two_stage_span_s": float(fin2.max())}
-        counts = cb.calvo_pool_counts(srv.slots)
-        assert counts["used"] == 0 and not srv.flight, "slots left allocated after the trace"
+            _, fin1 = dispatch.serve_trace_serial(pol, model, jobs, lambda i: srv.serve(jobs[i][2], jobs[i][3]))
+            out = srv.run_trace(pol, model, jobs, three_stage)
+            base = min(r["submit_s"] - a for r, a in zip(out, arr))      # the dispatcher's clock at the trace's time zero
+            fin1, fin2 = np.array(fin1), np.array([r["first_token_s"] - base for r in out])
+            st = srv.last_stats
+            res[name] = {"serial_ttft_s": float(np.mean(fin1 - arr)), "staged_ttft_s": float(np.mean(fin2 - arr)),
+                         "serial_met": float(np.mean(fin1 <= ddl)), "staged_met": float(np.mean(fin2 <= ddl)),
+                         "serial_span_s": float(fin1.max()), "staged_span_s": float(fin2.max()),
+                         "reactive": int(sum(r["reactive"] for r in out)),
+                         "alloc_wait_s": float(sum(r["alloc_wait_s"] for r in out)),
+                         "link_busy": (st["link_busy_s"] / st["link_span_s"]) if st["link_span_s"] > 0 else None}
         return res, model
     finally:
         srv.close()
@@ -275,17 +301,27 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--layers", type=int, default=8)
     ap.add_argument("--two-stage", action="store_true",
-                    help="compare request-by-request service with loading and computation as two stages")
+                    help="compare request-by-request service with loading and computation as two stages of the library's dispatcher")
+    ap.add_argument("--three-stage", action="store_true",
+                    help="the same with the emulated link in front: link, PCIe and compute as three stages")
+    ap.add_argument("--l3-gbps", type=float, default=50.0, help="rate of the emulated link in 1e9 bytes/s")
+    ap.add_argument("--depth", type=int, default=4, help="HBM pool size in requests of the largest size")
     ap.add_argument("--max-query", type=int, default=MAX_QRY)
     args = ap.parse_args()
-    if args.two_stage:
-        res, _ = study_two_stage(args.requests, args.load, args.seed, args.layers, args.max_query)
-        print(f"{args.requests} requests at {args.load:g} x capacity, {args.layers} layers, queries up to {args.max_query} tokens")
-        print(f"{'policy':<8}{'serial TTFT ms':>16}{'two-stage ms':>14}{'met':>6}{'met':>6}{'serial span ms':>16}{'two-stage ms':>14}")
+    if args.two_stage or args.three_stage:
+        res, _ = study_staged(args.requests, args.load, args.seed, args.layers, args.max_query, three_stage=args.three_stage,
+                              l3_GBps=args.l3_gbps, depth=args.depth)
+        what = f"three stages, link {args.l3_gbps:g} GB/s" if args.three_stage else "two stages"
+        print(f"{args.requests} requests at {args.load:g} x capacity, {args.layers} layers, queries up to {args.max_query} tokens, "
+              f"{what}, pool of {args.depth} requests")
+        print(f"{'policy':<8}{'serial TTFT ms':>16}{'staged ms':>12}{'met':>6}{'met':>6}{'serial span ms':>16}{'staged ms':>12}"
+              f"{'reactive':>10}{'link busy':>11}")
         for name, _ in POLICIES:
             r = res[name]
-            print(f"{name:<8}{r['serial_ttft_s'] * 1e3:>16.1f}{r['two_stage_ttft_s'] * 1e3:>14.1f}{r['serial_met'] * 100:>5.0f}%"
-                  f"{r['two_stage_met'] * 100:>5.0f}%{r['serial_span_s'] * 1e3:>16.1f}{r['two_stage_span_s'] * 1e3:>14.1f}")
+            busy = f"{r['link_busy'] * 100:.0f}%" if r["link_busy"] is not None else "-"
+            print(f"{name:<8}{r['serial_ttft_s'] * 1e3:>16.1f}{r['staged_ttft_s'] * 1e3:>12.1f}{r['serial_met'] * 100:>5.0f}%"
+                  f"{r['staged_met'] * 100:>5.0f}%{r['serial_span_s'] * 1e3:>16.1f}{r['staged_span_s'] * 1e3:>12.1f}"
+                  f"{r['reactive']:>10d}{busy:>11}")
         return
     res, _ = study(args.requests, args.load, args.seed, args.layers)
     print(f"{args.requests} requests at {args.load:g} x capacity, {args.layers} layers")

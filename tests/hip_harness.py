@@ -56,11 +56,12 @@ def make_requests(w: wl.Workload, host: torch.Tensor):
 
 
 def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_streams: int = 0,
-            scale: float = 0.0, append_suffix: bool = True, chunk_blocks=None, attn_fn=None):
+            scale: float = 0.0, append_suffix: bool = True, chunk_blocks=None, attn_fn=None, prepared: bool = False):
     """Whole path on cuda:0.  Returns (pool image as stored-dtype numpy [L][slots][elems],
     out as stored-dtype numpy [L][T][Hq][D]).  chunk_blocks: per-layer chunk sizes for the
     chunk-granular load (None: whole layers).  attn_fn: the binding function that runs the
-    attention stage (default calvo_prefill_attn)."""
+    attention stage (default calvo_prefill_attn).  prepared: the batch is prepared once
+    (calvo_batch_prepare) and every layer goes through calvo_prefill_attn_batch."""
     attn_fn = attn_fn or cb.calvo_prefill_attn
     s = w.shape
     dev = torch.device("cuda:0")
@@ -82,12 +83,20 @@ def run_hip(w: wl.Workload, staging_bytes: int = 0, n_staging: int = 0, n_copy_s
             cb.calvo_kv_ingest(ctx, reqs, 0, s.n_layers)
         else:
             cb.calvo_kv_ingest_chunked(ctx, reqs, 0, s.n_layers, chunk_blocks)
-        for l in range(s.n_layers):
-            attn_fn(ctx, l, q[l] if T else None, (ks[l] if append_suffix and T else None),
-                    (vs[l] if append_suffix and T else None), out[l] if T else None,
-                    reqs, w.cu_suffix, scale)
-        for l in range(s.n_layers):
-            assert cb.calvo_layer_event(ctx, l, cb.CALVO_EV_HOST_WAIT)
+        batch = cb.calvo_batch_prepare(ctx, reqs, w.cu_suffix) if prepared else None
+        try:
+            for l in range(s.n_layers):
+                args = (q[l] if T else None, (ks[l] if append_suffix and T else None),
+                        (vs[l] if append_suffix and T else None), out[l] if T else None)
+                if prepared:
+                    cb.calvo_prefill_attn_batch(ctx, batch, l, *args, scale)
+                else:
+                    attn_fn(ctx, l, *args, reqs, w.cu_suffix, scale)
+            for l in range(s.n_layers):
+                assert cb.calvo_layer_event(ctx, l, cb.CALVO_EV_HOST_WAIT)
+        finally:
+            if batch:
+                cb.calvo_batch_destroy(batch)
     finally:
         cb.calvo_destroy(ctx)          # waits for the compute stream too
     torch.cuda.synchronize()

@@ -1,16 +1,23 @@
-"""The dispatcher loops (dispatch.py) on a virtual clock, without a GPU: a request "runs" by moving
-the clock, so the loops' decisions can be compared with the library's replay of the same trace
-(calvo_sched_simulate), which in turn is pinned to the scheduling oracle."""
+"""The library's dispatcher (calvo_dispatch_*) as a dry run, without a GPU: with no context the stage
+threads run the same queues, policy order and slot admission on the host clock, the loading stage
+busy for a job's sim_load_s and the compute stage for its sim_comp_s.  Its decisions are compared
+with the scheduling oracle's staged replay (oracle/sched_oracle.py: both stages serve their
+highest-priority ready request) on traces whose decisions are separated from the events they depend
+on by several milliseconds, so thread wake-up jitter cannot change them; the serial baseline loop of
+dispatch.py runs on a virtual clock."""
 import math
+import time
 
 import numpy as np
 import pytest
 
+from oracle import sched_oracle as so
 from paper_2603_21257_amd import binding as cb
 from paper_2603_21257_amd import dispatch
 
 MODEL = (2.0e-6, 1.0e-3, 3.0e-5, 2.0e-3)
 POLICIES = [cb.CALVO_POLICY_FIFO, cb.CALVO_POLICY_SJF, cb.CALVO_POLICY_SJF_PT, cb.CALVO_POLICY_LSTF, cb.CALVO_POLICY_EDF]
+MARGIN = 6e-3
 
 
 class Clock:
@@ -44,77 +51,160 @@ def test_serial_loop_reproduces_the_replay(policy, seed):
     def run(i):
         clk.sleep(sum(cb.calvo_cost_estimate(MODEL, jobs[i])))
 
-    start, fin = dispatch.serve_trace(policy, MODEL, jobs, run, clock=clk, sleep=clk.sleep)
+    start, fin = dispatch.serve_trace_serial(policy, MODEL, jobs, run, clock=clk, sleep=clk.sleep)
     s0, f0 = cb.calvo_sched_simulate(policy, MODEL, jobs, pipelined=0)
     assert np.allclose(start, s0, atol=1e-9) and np.allclose(fin, f0, atol=1e-9)
 
 
+def staged_trace(policy, n=6):
+    """A small trace (arrival, deadline, ctx tokens, query tokens), stage times of 30..100 ms, whose staged
+    replay takes every decision at least MARGIN away from any arrival or end of loading that could
+    change it, and between priorities that differ.  Deterministic: the first seed that qualifies."""
+    model = (1.0e-6, 0.0, 1.0e-4, 0.0)                     # 30000..100000 ctx tokens, 300..1000 query tokens
+    for seed in range(4000):
+        rng = np.random.default_rng(seed)
+        arr = np.sort(rng.uniform(0.0, 0.3, n))
+        arr[0] = 0.0
+        jobs = []
+        for a in arr:
+            ctx, qry = int(rng.integers(30000, 100000)), int(rng.integers(300, 1000))
+            jobs.append((float(a), float(a) + float(rng.uniform(0.2, 1.0)), ctx, qry))
+        start, fin = so.simulate_staged(policy, model, jobs)
+        load_end = [start[i] + so.estimate(model, jobs[i])[0] for i in range(n)]
+        comp_start = [fin[i] - so.estimate(model, jobs[i])[1] for i in range(n)]
+        events = list(arr[1:]) + load_end
+        decisions = start[1:] + comp_start
+        gap = min(abs(d - e) for d in decisions for e in events if abs(d - e) > 1e-12)
+        pri = sorted(so.priority(policy, model, j) for j in jobs)
+        if gap >= MARGIN and min(np.diff(arr)) >= MARGIN and all(b - a > 1e-6 for a, b in zip(pri, pri[1:])):
+            return model, jobs
+    raise AssertionError("no seed gives a trace with well-separated decisions")
+
+
 @pytest.mark.parametrize("policy", POLICIES)
-def test_two_stage_loop_follows_the_two_stage_replay(policy):
-    """A two-stage server on the virtual clock: loading one request at a time, computation in loading
-    order as soon as the request is loaded.  The loop only notices events when it polls, so its times
-    trail the replay by at most one poll interval per decision."""
-    jobs = trace(3, n=24)
+def test_dry_run_takes_the_decisions_of_the_staged_replay(policy):
+    model, jobs = staged_trace(policy)
     n = len(jobs)
-    clk = Clock()
-    poll = 1e-4
-    load_end, comp_end = [math.inf] * n, [math.inf] * n
-    comp_free = [0.0]
-
-    def try_issue(i):
-        t_load, t_comp = cb.calvo_cost_estimate(MODEL, jobs[i])
-        load_end[i] = clk.t + t_load
-        comp_end[i] = max(load_end[i], comp_free[0]) + t_comp
-        comp_free[0] = comp_end[i]
-        return True
-
-    start, fin = dispatch.serve_trace_two_stage(policy, MODEL, jobs, try_issue, lambda i: clk.t >= load_end[i],
-                                                lambda i: clk.t >= comp_end[i], clock=clk, sleep=clk.sleep, poll_s=poll)
-    s1, f1 = cb.calvo_sched_simulate(policy, MODEL, jobs, pipelined=1)
-    order_loop, order_replay = np.argsort(start, kind="stable"), np.argsort(s1, kind="stable")
-    if list(order_loop) == list(order_replay):             # same decisions: times agree up to the polling lag
-        assert np.all(np.array(fin) >= f1 - 1e-9) and np.all(np.array(fin) - f1 <= 3 * n * poll)
-    else:                                                   # a poll-sized lag flipped a near-tie: totals still agree
-        assert abs(max(fin) - f1.max()) <= 3 * n * poll + max(sum(cb.calvo_cost_estimate(MODEL, j)) for j in jobs)
-    assert sorted(order_loop) == list(range(n))
-
-
-def test_two_stage_loop_retries_a_request_that_cannot_be_issued_yet():
-    jobs = [(0.0, math.inf, 1000, 10), (0.0, math.inf, 2000, 10)]
-    clk = Clock()
-    refused = [3]                                           # the first three attempts find no room
-    ends = {}
-
-    def try_issue(i):
-        if refused[0] > 0:
-            refused[0] -= 1
-            return False
-        ends[i] = clk.t + 0.01
-        return True
-
-    start, fin = dispatch.serve_trace_two_stage(cb.CALVO_POLICY_FIFO, MODEL, jobs, try_issue, lambda i: clk.t >= ends[i],
-                                                lambda i: clk.t >= ends[i] + 0.005, clock=clk, sleep=clk.sleep, poll_s=1e-4)
-    assert refused[0] == 0 and start[0] >= 3e-4 - 1e-12 and start[1] >= start[0] + 0.01 - 1e-9
-    assert fin[0] >= 0.015 and fin[1] >= fin[0]
+    with dispatch.Dispatcher(None, policy, model) as d:
+        t0 = time.perf_counter()
+        res = dispatch.serve_trace(
+            d, [j[0] for j in jobs],
+            lambda i: dict(n_prefix_blocks=jobs[i][2] // 16, suffix_len=jobs[i][3], deadline_s=jobs[i][1] - jobs[i][0],
+                           sim_load_s=so.estimate(model, jobs[i])[0], sim_comp_s=so.estimate(model, jobs[i])[1]))
+        assert time.perf_counter() - t0 < 5.0
+        st = d.stats()
+    assert st["jobs_submitted"] == n and st["jobs_done"] == n
+    # replay with the submission times the dispatcher saw
+    base = res[0]["submit_s"]
+    seen = [(r["submit_s"] - base, r["submit_s"] - base + (j[1] - j[0]), j[2], j[3]) for r, j in zip(res, jobs)]
+    assert max(abs(s[0] - j[0]) for s, j in zip(seen, jobs)) < MARGIN / 2, "the host could not keep the arrival times"
+    start, fin = so.simulate_staged(policy, model, seen)
+    got_start = [r["load_start_s"] - base for r in res]
+    got_fin = [r["first_token_s"] - base for r in res]
+    got_comp = [r["compute_start_s"] - base for r in res]
+    assert list(np.argsort(got_start)) == list(np.argsort(start)), "loading stage served another order"
+    want_comp = [fin[i] - so.estimate(model, seen[i])[1] for i in range(n)]
+    assert list(np.argsort(got_comp)) == list(np.argsort(want_comp)), "compute stage served another order"
+    lag = np.array(got_fin) - np.array(fin)                  # threads wake a little late, never early
+    assert lag.min() > -1e-3 and lag.max() < MARGIN * 2, lag
+    # the library's own staged replay says the same
+    s2, f2 = cb.calvo_sched_simulate(policy, model, seen, pipelined=2)
+    assert np.allclose(s2, start, atol=1e-12) and np.allclose(f2, fin, atol=1e-12)
+    for r in res:
+        assert r["status"] == 0 and not r["reactive"]
+        assert r["submit_s"] <= r["load_start_s"] <= r["load_end_s"] <= r["compute_start_s"] <= r["first_token_s"]
 
 
-def test_pooled_loop_grants_waits_and_releases():
-    """Three requests of 6 slots on a pool of 10: the second has to wait until the first lets go."""
+def test_dry_run_overlaps_loading_with_the_previous_computation():
+    """Two stages on different requests at once: n equal jobs take load + n * max(load, comp) + ..., not n * (load + comp)."""
+    with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO) as d:
+        ids = [d.submit(suffix_len=1, sim_load_s=0.03, sim_comp_s=0.03) for _ in range(5)]
+        res = [d.wait(i) for i in ids]
+    span = res[-1]["first_token_s"] - res[0]["load_start_s"]
+    assert 0.03 * 6 - 1e-3 <= span < 0.03 * 6 + 0.03, span       # serial service would take 0.30 s
+    for a, b in zip(res, res[1:]):
+        assert b["load_start_s"] < a["first_token_s"]             # the next request loads while this one computes
+
+
+def test_dry_run_slot_admission_is_proactive_then_reactive():
+    """Three requests of 6 slots on a pool of 10: the first is granted at issue; the second has to wait in the
+    loading stage until the first is released, the third until the second is."""
     pool = cb.calvo_pool_create(10)
     try:
-        jobs = [(0.0, math.inf, 100, 1), (0.0, math.inf, 100, 1), (0.0, math.inf, 100, 1)]
-        clk = Clock()
-        seen = []
+        with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool) as d:
+            ids = [d.submit(n_prefix_blocks=5, suffix_len=16, sim_load_s=0.01, sim_comp_s=0.01) for _ in range(3)]
+            r0 = d.wait(ids[0])
+            t0 = d.table(ids[0])
+            assert len(t0) == 6 and len(set(t0.tolist())) == 6 and not r0["reactive"]
+            assert cb.calvo_pool_counts(pool)["waiting"] == 1
+            assert d.poll(ids[1]) is None
+            with pytest.raises(cb.CalvoError):
+                d.table(ids[1])                                   # no slots yet
+            time.sleep(0.05)
+            assert d.poll(ids[1]) is None                         # still waiting: nothing was released
+            d.release(ids[0])
+            r1 = d.wait(ids[1])
+            assert r1["reactive"] and r1["alloc_wait_s"] >= 0.05
+            t1 = d.table(ids[1])
+            assert len(set(t1.tolist())) == 6
+            time.sleep(0.02)
+            d.release(ids[1])
+            r2 = d.wait(ids[2])
+            assert r2["reactive"] and r2["alloc_wait_s"] >= 0.02
+            assert r2["load_end_s"] >= r1["first_token_s"]
+            with pytest.raises(cb.CalvoError):
+                d.release(ids[1])                                 # once per job
+            # job 2 is not released by hand: the dispatcher gives its slots back when it goes
+        assert cb.calvo_pool_counts(pool) == {"free": 10, "used": 0, "refs": 0, "waiting": 0}
+    finally:
+        cb.calvo_pool_destroy(pool)
 
-        def run(i, table):
-            assert len(table) == 6 and len(set(table.tolist())) == 6
-            seen.append(set(table.tolist()))
-            clk.sleep(0.01)
 
-        start, fin, reactive, waited = dispatch.serve_trace_pooled(cb.CALVO_POLICY_FIFO, None, jobs, pool, [6, 6, 6], run,
-                                                                  hold_s=[0.05, 0.05, 0.05], clock=clk, sleep=clk.sleep)
-        assert reactive == [False, True, True]
-        assert waited[1] >= 0.05 - 1e-9 and waited[2] >= 0.05 - 1e-9
-        assert cb.calvo_pool_counts(pool)["used"] == 0
+def test_dry_run_shared_run_is_referenced_per_job():
+    pool = cb.calvo_pool_create(16)
+    try:
+        run = cb.calvo_pool_reserve(pool, 4)                      # a resident prefix run, held by its owner
+        with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool) as d:
+            a = d.submit(block_table=run, n_prefix_blocks=6, n_shared=4, suffix_len=16, sim_load_s=0.005, sim_comp_s=0.005)
+            b = d.submit(block_table=run, n_prefix_blocks=4, n_shared=4, suffix_len=20, sim_load_s=0.005, sim_comp_s=0.005)
+            d.wait(a), d.wait(b)
+            ta, tb = d.table(a), d.table(b)
+            assert list(ta[:4]) == list(run) and list(tb[:4]) == list(run)
+            assert len(ta) == 7 and len(tb) == 6 and not set(ta[4:].tolist()) & set(tb[4:].tolist())
+            assert cb.calvo_pool_counts(pool)["refs"] == 4 * 3 + 3 + 2
+            d.release(a)
+            assert cb.calvo_pool_counts(pool)["refs"] == 4 * 2 + 2
+            d.release(b)
+        assert cb.calvo_pool_counts(pool) == {"free": 12, "used": 4, "refs": 4, "waiting": 0}
+        cb.calvo_pool_release(pool, run)
+    finally:
+        cb.calvo_pool_destroy(pool)
+
+
+def test_dispatcher_refuses_bad_arguments():
+    with pytest.raises(cb.CalvoError):
+        cb.calvo_dispatch_create(None, 9)
+    with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO) as d:
+        for bad in (dict(n_prefix_blocks=-1), dict(suffix_len=-1), dict(n_prefix_blocks=2, n_shared=3),
+                    dict(sim_load_s=math.nan), dict(sim_comp_s=-1.0), dict(sim_load_s=math.inf)):
+            with pytest.raises(cb.CalvoError):
+                d.submit(**bad)
+        with pytest.raises(cb.CalvoError):
+            d.wait(0)                                             # nothing was queued by the refused calls
+        i = d.submit(sim_load_s=0.02, sim_comp_s=0.0)
+        with pytest.raises(cb.CalvoError):
+            d.release(i)                                          # not finished yet
+        d.wait(i)
+        d.release(i)
+        with pytest.raises(cb.CalvoError):
+            d.poll(7)
+    pool = cb.calvo_pool_create(4)
+    try:
+        with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool) as d:
+            i = d.submit(n_prefix_blocks=8, suffix_len=1, sim_load_s=0.0, sim_comp_s=0.0)     # can never fit
+            with pytest.raises(cb.CalvoError):
+                d.wait(i)
+            with pytest.raises(cb.CalvoError):
+                d.poll(i)
     finally:
         cb.calvo_pool_destroy(pool)

@@ -38,6 +38,42 @@ def test_bf16_mfma_single_request(P, S):
     check(w)
 
 
+@pytest.mark.parametrize("lens,shared,chunks", [
+    ([(160, 77)], 0, None), ([(1024, 64), (48, 1), (0, 130)], 0, None), ([(8192, 40)], 0, None),
+    ([(17 * 16, 40), (9 * 16, 20)], 2, None), ([(64 * 16, 90)], 0, [8, 0]), ([(320, 0)], 0, None)])
+def test_prepared_batch_gives_the_result_of_the_per_call_path(lens, shared, chunks):
+    """calvo_batch_prepare + calvo_prefill_attn_batch (validation, planning and descriptor upload
+    once per batch) against the oracle, and bit for bit against calvo_prefill_attn: single requests,
+    a batch, split-KV pieces, a shared run, a layer loaded in chunks (planned per call), an empty suffix."""
+    shape = wl.Shape(2, 8, 2, 128, "bf16", sum(-(-(p + s) // 16) for p, s in lens) + 8)
+    w = wl.make_custom(shape, lens, seed=311 + len(lens), shared_blocks=shared)
+    kw = dict(staging_bytes=16 * shape.blk_bytes, chunk_blocks=chunks)
+    pool_p, out_p = hh.run_hip(w, prepared=True, **kw)
+    pool_c, out_c = hh.run_hip(w, **kw)
+    pool_o, out_o = hh.run_oracle(w)
+    hh.assert_pool_bit_exact(pool_p, pool_o)
+    hh.assert_attn_close(out_p, out_o, "bf16")
+    assert np.array_equal(out_p, out_c)
+
+
+def test_prepared_batch_fp32_and_bad_requests():
+    w = wl.make_custom(wl.Shape(2, 6, 3, 40, "f32", 64), [(64, 37), (0, 50), (160, 5)], seed=19)
+    pool_p, out_p = hh.run_hip(w, prepared=True, scale=0.2)
+    pool_o, out_o = hh.run_oracle(w, scale=0.2)
+    hh.assert_pool_bit_exact(pool_p, pool_o)
+    hh.assert_attn_close(out_p, out_o, "f32")
+    # a slot outside the pool is refused when the batch is prepared: no handle, nothing queued
+    pool = torch.zeros(64 * w.shape.blk_elems * 2, dtype=torch.float32, device="cuda:0")
+    ctx = cb.calvo_create(2, 6, 3, 40, cb.CALVO_F32, 64, pool)
+    try:
+        bad = cb.make_request(None, 0, np.array([1, 2, 64], np.int32), 2, 5, 2)
+        with pytest.raises(cb.CalvoError) as ei:
+            cb.calvo_batch_prepare(ctx, [bad], np.array([0, 5], np.int32))
+        assert ei.value.code == cb.CALVO_EINVAL and "outside the pool" in str(ei.value)
+    finally:
+        cb.calvo_destroy(ctx)
+
+
 def _scale_prefix_keys(w, gain):
     """Multiply the K rows of the cached prefix by gain(position) (re-rounded to bf16), in place."""
     from oracle import calvo_oracle as orc
