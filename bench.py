@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--tail-layers", type=int, default=6)
     ap.add_argument("--no-cfg4-leg", action="store_true",
                     help="skip the short run of the attention-bound 8-request batch (workload 4) that the default run appends")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="diagnostic, with --mode attn: all inputs zero instead of N(0,1) - the matrix pipes then run at the "
+                         "nominal clock, which shows the kernel's structural duty apart from the power limit")
     ap.add_argument("--leg", action="store_true", help="(internal) run as the appended leg: timing of the step only")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -115,6 +118,11 @@ def main():
     ks = wl.fill_normal_(torch.empty((L, T, s.n_kv_heads, s.head_dim), dtype=tdt, device=dev), w.seed + 12)
     vs = wl.fill_normal_(torch.empty((L, T, s.n_kv_heads, s.head_dim), dtype=tdt, device=dev), w.seed + 13)
     out = torch.empty((L, T, s.n_q_heads, s.head_dim), dtype=tdt, device=dev)
+    if args.zero_data:
+        if args.mode != "attn":
+            sys.exit("--zero-data is a diagnostic of --mode attn")
+        for t in (host, q, ks, vs):
+            t.zero_()
     torch.cuda.synchronize()
     log(f"[bench] inputs resident after {time.perf_counter() - t_setup:.1f} s")
 
@@ -206,7 +214,8 @@ def main():
             for _ in range(args.warmup):
                 fn()
             t = [timed(fn) for _ in range(args.steps)]
-            log(f"[bench] mode {args.mode}: {statistics.mean(t):.3f} ms per pass over {L} layers")
+            log(f"[bench] mode {args.mode}{' (zero data)' if args.zero_data else ''}: {statistics.mean(t):.3f} ms per pass over {L} layers"
+                + (f" = {w.attn_flop() / statistics.mean(t) / 1e9:.1f} TFLOP/s" if args.mode == "attn" else ""))
             return
         # ---- stage times in isolation (context for the overlap figure, and the choice of the chunked tail)
         ingest_only()
