@@ -41,6 +41,28 @@ def test_struct_layouts_match_header_order():
     assert ctypes.sizeof(cb.calvo_l3_stats) == 40
 
 
+def test_struct_layouts_match_what_a_c_compiler_makes_of_the_header(tmp_path):
+    """Size and every field offset of every struct of the binding against gcc's view of include/calvo.h."""
+    import subprocess
+    structs = [cb.calvo_config, cb.calvo_request, cb.calvo_l3_config, cb.calvo_l3_stats, cb.calvo_cost_model, cb.calvo_job,
+               cb.calvo_dispatch_config, cb.calvo_dispatch_job, cb.calvo_dispatch_result, cb.calvo_dispatch_stats]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "calvo.h"', 'int main(void) {']
+    for st in structs:
+        lines.append(f'  printf("{st.__name__} %zu\\n", sizeof({st.__name__}));')
+        for name, _ in st._fields_:
+            lines.append(f'  printf("{st.__name__}.{name} %zu\\n", offsetof({st.__name__}, {name}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(ln.split() for ln in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st in structs:
+        assert int(out[st.__name__]) == ctypes.sizeof(st), st.__name__
+        for name, _ in st._fields_:
+            assert int(out[f"{st.__name__}.{name}"]) == getattr(st, name).offset, f"{st.__name__}.{name}"
+
+
 @pytest.mark.parametrize("kw,frag", [
     (dict(pool=0), "pool is NULL"),
     (dict(n_q_heads=8, n_kv_heads=3), "multiple of n_kv_heads"),

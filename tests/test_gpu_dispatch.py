@@ -252,6 +252,17 @@ def test_two_stages_with_a_small_pool_and_a_shared_prefix_run():
     assert res[1]["alloc_wait_s"] >= 0.1
 
 
+@pytest.mark.parametrize("three_stage", [False, True])
+def test_degenerate_jobs_pass_through_every_stage(three_stage):
+    """A request with nothing to load (no prefix), one with nothing to compute (no query tokens) and an ordinary one:
+    each passes every stage, results and loaded bytes as the oracle has them."""
+    lens = [(0, 45), (48 * 16, 0), (32 * 16, 16), (0, 16)]
+    res, st = _dispatcher_case(three_stage, lens, 128, [0.0] * 4, seed=99)
+    assert all(r["status"] == 0 and not r["reactive"] for r in res)
+    for r in res:
+        assert r["submit_s"] <= r["load_start_s"] <= r["load_end_s"] <= r["first_token_s"]
+
+
 @pytest.mark.timing
 def test_the_link_stays_busy_while_other_requests_compute():
     """Link-bound service: four requests of 96 MiB each behind a 4 GB/s link, ample HBM.  The link
