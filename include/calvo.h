@@ -451,7 +451,8 @@ int calvo_dispatch_create(calvo_ctx* ctx, const calvo_dispatch_config* cfg, calv
  * is not page-locked in two-stage mode; CALVO_ENOMEM if the job can never fit the pool. */
 int calvo_dispatch_submit(calvo_dispatcher* d, const calvo_dispatch_job* job, int64_t* id);
 /* Blocks until the job's last attention launch has finished (its first token could be sampled) or the
- * job has failed; returns the job's status and fills res (may be NULL). */
+ * job has failed; returns the job's status - calvo_last_error then holds what the failing call inside
+ * the stage thread reported - and fills res (may be NULL). */
 int calvo_dispatch_wait(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* res);
 /* The same without blocking: CALVO_ENOTREADY while the job is under way (res holds what is known). */
 int calvo_dispatch_poll(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* res);
@@ -464,9 +465,9 @@ int calvo_dispatch_table(calvo_dispatcher* d, int64_t id, int32_t* table, int32_
  * call: a caller that uses a pool smaller than its working set must release finished jobs. */
 int calvo_dispatch_release(calvo_dispatcher* d, int64_t id);
 int calvo_dispatch_stats_get(calvo_dispatcher* d, calvo_dispatch_stats* stats);
-/* Waits for every submitted job to finish - jobs that wait for slots need calvo_dispatch_release from
- * another thread, or this call does not return - stops the threads, waits for the streams, gives back
- * the slots of jobs that were not released, and frees the dispatcher.  Must precede calvo_destroy. */
+/* Waits for every submitted job to finish - finished jobs that were not released are released by this
+ * call, so jobs that wait for their slots go on - stops the threads, waits for the streams and frees
+ * the dispatcher.  Must precede calvo_destroy. */
 int calvo_dispatch_destroy(calvo_dispatcher* d);
 
 /* Measurement helper: duration in milliseconds of the most recent attention kernel queued by

@@ -41,6 +41,7 @@ struct Job {
   hipEvent_t ev_done = nullptr;
   calvo_batch* batch = nullptr;
   calvo_dispatch_result res{};
+  std::string err;                      // what the failing call said (the stage threads have their own last-error text)
 };
 
 struct Chunk {
@@ -96,8 +97,11 @@ int pick_job(calvo_dispatcher* d, const std::vector<char>& eligible) {
   return idx;
 }
 
-void fail_job(calvo_dispatcher* d, Job* j, int status) {      // d->mu held
-  if (j->res.status == CALVO_OK) j->res.status = status;
+void fail_job(calvo_dispatcher* d, Job* j, int status) {      // d->mu held; called on the thread whose call failed
+  if (j->res.status == CALVO_OK) {
+    j->res.status = status;
+    j->err = calvo_last_error();
+  }
   if (!j->finished) {
     j->finished = true;
     j->res.first_token_s = d->now();
@@ -567,7 +571,7 @@ int calvo_dispatch_wait(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* 
   if (!j) return fail(CALVO_EINVAL, "unknown job %lld", (long long)id);
   d->cv.wait(lk, [&] { return j->finished; });
   if (res) *res = j->res;
-  if (j->res.status != CALVO_OK) return fail(j->res.status, "job %lld failed in the dispatcher", (long long)id);
+  if (j->res.status != CALVO_OK) return fail(j->res.status, "job %lld failed: %s", (long long)id, j->err.c_str());
   return CALVO_OK;
 }
 
@@ -578,7 +582,8 @@ int calvo_dispatch_poll(calvo_dispatcher* d, int64_t id, calvo_dispatch_result* 
   if (!j) return fail(CALVO_EINVAL, "unknown job %lld", (long long)id);
   if (res) *res = j->res;
   if (!j->finished) return CALVO_ENOTREADY;
-  return j->res.status;
+  if (j->res.status != CALVO_OK) return fail(j->res.status, "job %lld failed: %s", (long long)id, j->err.c_str());
+  return CALVO_OK;
 }
 
 int calvo_dispatch_table(calvo_dispatcher* d, int64_t id, int32_t* table, int32_t capacity, int32_t* n) {
@@ -629,13 +634,22 @@ int calvo_dispatch_stats_get(calvo_dispatcher* d, calvo_dispatch_stats* st) {
 int calvo_dispatch_destroy(calvo_dispatcher* d) {
   if (!d) return fail(CALVO_EINVAL, "dispatcher is NULL");
   {
-    // let the work that has been submitted finish, then stop the stages
+    // let the work that has been submitted finish, then stop the stages; finished jobs that nobody
+    // released give their slots back now, so that jobs which wait for slots can go on
     std::unique_lock<std::mutex> lk(d->mu);
-    d->cv.wait(lk, [&] {
-      for (auto& j : d->jobs)
-        if (!j->finished) return false;
-      return true;
-    });
+    for (;;) {
+      bool all = true;
+      for (auto& j : d->jobs) {
+        if (!j->finished) { all = false; continue; }
+        if (d->cfg.pool && j->granted && !j->released && j->n_tab > 0) {
+          (void)calvo_pool_release(d->cfg.pool, j->table.data(), j->n_tab);
+          j->released = true;
+          d->cv.notify_all();
+        }
+      }
+      if (all) break;
+      d->cv.wait_for(lk, std::chrono::milliseconds(2));
+    }
     d->stop = true;
   }
   d->cv.notify_all();
@@ -653,8 +667,6 @@ int calvo_dispatch_destroy(calvo_dispatcher* d) {
     batch_free_completed(j->batch);
     for (auto ev : j->ev_layer) if (ev) (void)hipEventDestroy(ev);
     if (j->ev_done) (void)hipEventDestroy(j->ev_done);
-    // a job that still holds slots gives them back with the dispatcher
-    if (d->cfg.pool && j->granted && !j->released && j->n_tab > 0) (void)calvo_pool_release(d->cfg.pool, j->table.data(), j->n_tab);
     if (d->cfg.pool && !j->granted && j->ticket >= 0) (void)calvo_pool_cancel(d->cfg.pool, j->ticket);
   }
   delete d;

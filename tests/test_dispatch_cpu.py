@@ -208,3 +208,34 @@ def test_dispatcher_refuses_bad_arguments():
                 d.poll(i)
     finally:
         cb.calvo_pool_destroy(pool)
+
+
+def test_destroy_releases_finished_jobs_so_that_waiting_ones_finish():
+    """Nobody releases anything: closing the dispatcher gives the finished jobs' slots back one after the other,
+    the jobs that wait for them run, and every slot is free afterwards."""
+    pool = cb.calvo_pool_create(10)
+    try:
+        d = dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool)
+        ids = [d.submit(n_prefix_blocks=5, suffix_len=16, sim_load_s=0.005, sim_comp_s=0.005) for _ in range(3)]
+        d.wait(ids[0])
+        t0 = time.perf_counter()
+        d.close()
+        assert time.perf_counter() - t0 < 5.0
+        assert cb.calvo_pool_counts(pool) == {"free": 10, "used": 0, "refs": 0, "waiting": 0}
+    finally:
+        cb.calvo_pool_destroy(pool)
+
+
+def test_a_failed_job_reports_what_the_stage_thread_saw():
+    pool = cb.calvo_pool_create(4)
+    try:
+        with dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool) as d:
+            run = np.array([9], np.int32)                         # not a slot of this pool: the admission is refused
+            i = d.submit(block_table=run, n_prefix_blocks=2, n_shared=1, suffix_len=1, sim_load_s=0.0, sim_comp_s=0.0)
+            with pytest.raises(cb.CalvoError) as ei:
+                d.wait(i)
+            assert ei.value.code == cb.CALVO_EINVAL and f"job {i} failed" in str(ei.value)
+            ok = d.submit(n_prefix_blocks=1, suffix_len=1, sim_load_s=0.0, sim_comp_s=0.0)   # the dispatcher goes on
+            assert d.wait(ok)["status"] == 0
+    finally:
+        cb.calvo_pool_destroy(pool)
