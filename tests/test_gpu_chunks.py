@@ -118,3 +118,40 @@ def test_attention_of_a_chunk_sees_only_landed_bytes():
     for l in range(3):
         want = hh.orc.prefill_attn_sampled(view[l], w.q[l], r.table, r.prefix_len, r.suffix_len, 16, rows)
         hh.assert_attn_close(out_g[l][rows], want, "bf16")
+
+
+@pytest.mark.parametrize("second", ["chunked", "whole"])
+def test_two_requests_interleaved_through_one_context(second):
+    """The readiness state of a layer belongs to the most recent loading call.  Here the second request's
+    loading call (another chunk size, or whole layers) is queued before the first request's attention
+    calls: the first request's launches are then planned with the later call's chunk geometry and wait
+    for the later call's events - later than necessary, never too early, because the loads are in order
+    on one stream.  Both requests' outputs and the pool bytes are the oracle's."""
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 256)
+    w = wl.make_custom(shape, [(97 * 16, 45), (40 * 16, 70)], seed=1400)
+    s = w.shape
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(s), s, dev)
+    host = hh.to_torch(w.host_kv, s, pin=True)
+    q, ks, vs = (hh.to_torch(a, s, dev) for a in (w.q, w.k_suffix, w.v_suffix))
+    out = torch.full((s.n_layers, w.total_suffix, s.n_q_heads, s.head_dim), float("nan"), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    ctx = cb.calvo_create(s.n_layers, s.n_q_heads, s.n_kv_heads, s.head_dim, cb.CALVO_BF16, s.pool_blocks, pool,
+                          staging_bytes=24 * s.blk_bytes)
+    try:
+        reqs = hh.make_requests(w, host)
+        cb.calvo_kv_ingest_chunked(ctx, [reqs[0]], 0, s.n_layers, [16, 16, 0])
+        if second == "chunked":
+            cb.calvo_kv_ingest_chunked(ctx, [reqs[1]], 0, s.n_layers, [6, 0, 10])
+        else:
+            cb.calvo_kv_ingest(ctx, [reqs[1]], 0, s.n_layers)
+        for i in (0, 1):
+            a, b = int(w.cu_suffix[i]), int(w.cu_suffix[i + 1])
+            for l in range(s.n_layers):
+                cb.calvo_prefill_attn(ctx, l, q[l, a:b], ks[l, a:b], vs[l, a:b], out[l, a:b], [reqs[i]], [0, b - a], 0.0)
+    finally:
+        cb.calvo_destroy(ctx)
+    torch.cuda.synchronize()
+    pool_o, out_o = hh.run_oracle(w)
+    hh.assert_pool_bit_exact(hh.to_numpy_stored(pool, s), pool_o)
+    hh.assert_attn_close(hh.to_numpy_stored(out, s), out_o, "bf16")
