@@ -395,7 +395,7 @@ void comp_main(calvo_dispatcher* d) {
     if (d->stop) return;
     if (rc != CALVO_OK) fail_job(d, j, rc);
     else if (e != hipSuccess) { (void)hipGetLastError(); fail_job(d, j, CALVO_EHIP); }
-    else d->done_q.push_back(j);
+    else if (j->res.status == CALVO_OK) d->done_q.push_back(j);     // a job that failed while it loaded is finished already
     d->cv.notify_all();
   }
 }
