@@ -52,15 +52,16 @@ class Dispatcher:
 
 
 def serve_trace(d: Dispatcher, arrivals: Sequence[float], make_job: Callable[[int], dict], hold_s: Optional[Sequence[float]] = None,
-                on_finish: Optional[Callable[[int, int, dict], None]] = None, clock: Callable[[], float] = time.perf_counter,
-                sleep: Callable[[float], None] = time.sleep):
+                on_finish: Optional[Callable[[int, int, dict], None]] = None, on_release: Optional[Callable[[int], None]] = None,
+                clock: Callable[[], float] = time.perf_counter, sleep: Callable[[float], None] = time.sleep):
     """Submits request i (keyword arguments of calvo_dispatch_submit from make_job(i)) at arrivals[i]
     seconds after entry, in the order of arrivals, and returns the list of results
     (calvo_dispatch_result as dicts, times on the dispatcher's clock) indexed like arrivals.
 
     hold_s[i]: request i keeps its HBM slots this long after its first token (the decode phase that
     follows the prefill), then they are released; None releases at the first token.  on_finish(i,
-    job id, result) runs when request i has finished, before its slots are released.
+    job id, result) runs when request i has finished, before its slots are released; on_release(i) right
+    before they are.
     """
     n = len(arrivals)
     order = sorted(range(n), key=lambda i: (arrivals[i], i))
@@ -82,6 +83,8 @@ def serve_trace(d: Dispatcher, arrivals: Sequence[float], make_job: Callable[[in
             holders.append((clock() - t0 + (float(hold_s[i]) if hold_s is not None else 0.0), i))
         now = clock() - t0
         for when, i in [h for h in holders if h[0] <= now]:
+            if on_release:
+                on_release(i)
             d.release(ids[i])
             holders.remove((when, i))
 

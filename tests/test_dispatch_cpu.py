@@ -239,3 +239,39 @@ def test_a_failed_job_reports_what_the_stage_thread_saw():
             assert d.wait(ok)["status"] == 0
     finally:
         cb.calvo_pool_destroy(pool)
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+def test_dry_run_random_trace_with_a_tight_pool_drains(policy):
+    """60 jobs of random size on a pool that holds about three of them, random hold times: every job gets
+    distinct slots while it holds them, every job finishes, nothing is left allocated."""
+    rng = np.random.default_rng(100 + policy)
+    n = 60
+    blocks = rng.integers(1, 40, n)
+    suffix = rng.integers(0, 64, n)
+    need = [int(b) + -(-int(s) // 16) for b, s in zip(blocks, suffix)]
+    arrivals = np.sort(rng.uniform(0.0, 0.15, n))
+    deadlines = rng.uniform(0.05, 0.5, n)
+    pool = cb.calvo_pool_create(100)
+    live = {}
+    try:
+        with dispatch.Dispatcher(None, policy, (1e-6, 0.0, 1e-5, 0.0), pool=pool) as d:
+            def on_finish(i, jid, res):
+                t = d.table(jid)
+                assert len(t) == need[i] and len(set(t.tolist())) == need[i] and t.min() >= 0 and t.max() < 100
+                for j, other in live.items():                      # jobs that still hold slots share none with this one
+                    assert not set(t.tolist()) & other, (i, j)
+                live[i] = set(t.tolist())
+
+            t0 = time.perf_counter()
+            res = dispatch.serve_trace(
+                d, list(arrivals),
+                lambda i: dict(n_prefix_blocks=int(blocks[i]), suffix_len=int(suffix[i]), deadline_s=float(deadlines[i]),
+                               sim_load_s=float(blocks[i]) * 1e-4, sim_comp_s=float(suffix[i]) * 2e-5),
+                hold_s=list(rng.uniform(0.0, 0.01, n)), on_finish=on_finish, on_release=lambda i: live.pop(i))
+            assert time.perf_counter() - t0 < 20.0
+        assert not live and all(r is not None and r["status"] == 0 for r in res)
+        assert sum(r["reactive"] for r in res) > 0, "the pool was never short: the case does not test the reactive path"
+        assert cb.calvo_pool_counts(pool) == {"free": 100, "used": 0, "refs": 0, "waiting": 0}
+    finally:
+        cb.calvo_pool_destroy(pool)
