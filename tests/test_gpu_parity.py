@@ -40,7 +40,7 @@ def test_bf16_mfma_single_request(P, S):
 
 @pytest.mark.parametrize("lens,shared,chunks", [
     ([(160, 77)], 0, None), ([(1024, 64), (48, 1), (0, 130)], 0, None), ([(8192, 40)], 0, None),
-    ([(17 * 16, 40), (9 * 16, 20)], 2, None), ([(64 * 16, 90)], 0, [8, 0]), ([(320, 0)], 0, None)])
+    ([(17 * 16, 40), (9 * 16, 20)], 2, None), ([(64 * 16, 90)], 0, [8, 0]), ([(64 * 16, 90)], 0, [8, 24]), ([(320, 0)], 0, None)])
 def test_prepared_batch_gives_the_result_of_the_per_call_path(lens, shared, chunks):
     """calvo_batch_prepare + calvo_prefill_attn_batch (validation, planning and descriptor upload
     once per batch) against the oracle, and bit for bit against calvo_prefill_attn: single requests,
@@ -54,6 +54,44 @@ def test_prepared_batch_gives_the_result_of_the_per_call_path(lens, shared, chun
     hh.assert_pool_bit_exact(pool_p, pool_o)
     hh.assert_attn_close(out_p, out_o, "bf16")
     assert np.array_equal(out_p, out_c)
+
+
+def test_prepared_batch_is_reused_over_steps_and_chunk_geometries():
+    """One prepared batch serves several steps whose layers are loaded whole or in chunks of different sizes:
+    the launches that follow a chunking are planned the first time it is seen and found again afterwards.
+    Every step gives the oracle's result."""
+    shape = wl.Shape(3, 8, 2, 128, "bf16", 160)
+    w = wl.make_custom(shape, [(70 * 16, 50), (33 * 16, 17)], seed=77)
+    s = w.shape
+    dev = torch.device("cuda:0")
+    pool = hh.to_torch(hh.sentinel_pool_np(s), s, dev)
+    host = hh.to_torch(w.host_kv, s, pin=True)
+    q, ks, vs = (hh.to_torch(a, s, dev) for a in (w.q, w.k_suffix, w.v_suffix))
+    out = torch.empty((s.n_layers, w.total_suffix, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+    pool_o, out_o = hh.run_oracle(w)
+    ctx = cb.calvo_create(s.n_layers, s.n_q_heads, s.n_kv_heads, s.head_dim, cb.CALVO_BF16, s.pool_blocks, pool,
+                          staging_bytes=32 * s.blk_bytes)
+    try:
+        reqs = hh.make_requests(w, host)
+        batch = cb.calvo_batch_prepare(ctx, reqs, w.cu_suffix)
+        try:
+            for step, chunks in enumerate([[8, 8, 20], None, [0, 12, 12], [8, 0, 20], [8, 8, 20]]):
+                pool.copy_(hh.to_torch(hh.sentinel_pool_np(s), s, dev))
+                out.fill_(float("nan"))
+                torch.cuda.synchronize()
+                if chunks is None:
+                    cb.calvo_kv_ingest(ctx, reqs, 0, s.n_layers)
+                else:
+                    cb.calvo_kv_ingest_chunked(ctx, reqs, 0, s.n_layers, chunks)
+                for l in range(s.n_layers):
+                    cb.calvo_prefill_attn_batch(ctx, batch, l, q[l], ks[l], vs[l], out[l], 0.0)
+                torch.cuda.synchronize()
+                hh.assert_pool_bit_exact(hh.to_numpy_stored(pool, s), pool_o)
+                hh.assert_attn_close(hh.to_numpy_stored(out, s), out_o, "bf16")
+        finally:
+            cb.calvo_batch_destroy(batch)
+    finally:
+        cb.calvo_destroy(ctx)
 
 
 def test_prepared_batch_fp32_and_bad_requests():
