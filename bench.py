@@ -80,6 +80,13 @@ def main():
     ap.add_argument("--zero-data", action="store_true",
                     help="diagnostic, with --mode attn: all inputs zero instead of N(0,1) - the matrix pipes then run at the "
                          "nominal clock, which shows the kernel's structural duty apart from the power limit")
+    ap.add_argument("--gap-ms", type=float, default=0.0,
+                    help="diagnostic, with --mode attn: the GPU idles this long before every attention launch (the clock "
+                         "has to ramp up again after an idle gap; the kernel time is reported)")
+    ap.add_argument("--no-alap", action="store_true",
+                    help="queue every layer's attention behind its own layer's loading signal (default when attention "
+                         "bounds the step).  Default for load-bound steps: the attention chain starts as late as it can "
+                         "and still end with the last layer, so that its launches run back to back")
     ap.add_argument("--leg", action="store_true", help="(internal) run as the appended leg: timing of the step only")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -175,6 +182,23 @@ def main():
             plan["chunk_blocks"] = [0] * (L - nt) + [per] * nt
 
     host_trace = []
+    # after[l]: the layer whose loading signal layer l's attention waits for (l itself: as soon as its own blocks are in)
+    plan["after"] = list(range(L))
+
+    def set_alap(t_ing_ms, t_att_ms):
+        """Load-bound step: a layer's attention is shorter than a layer's load, so launches that each wait for their
+        own layer run with idle gaps between them, and after every gap the clock has to ramp up again (measured:
+        --mode attn --gap-ms).  The compute chain loses nothing by starting later: the whole-layer launches are
+        queued so that they run back to back and reach the last of them when its blocks land.  With n such layers
+        (the layers before the chunk-granular tail, which keeps following its own chunks), layer j lands at
+        (j + 1) t_load and the chain has to be at l by n t_load - (n - 1 - l) t_att, so layer l waits for layer
+        j = n - 1 - ceil((n - 1 - l) rho), rho = t_att / t_load per layer, taken 6 % high (the first launches
+        after the idle start are slow)."""
+        import math
+        rho = min(1.0, 1.06 * t_att_ms / max(t_ing_ms, 1e-9))
+        cbs = plan["chunk_blocks"] or [0] * L
+        n = next((l for l in range(L) if cbs[l]), L)
+        plan["after"] = [max(l, n - 1 - math.ceil((n - 1 - l) * rho)) if l < n else l for l in range(L)]
 
     def step():
         t0 = time.perf_counter()
@@ -184,6 +208,8 @@ def main():
             cb.calvo_kv_ingest_chunked(ctx, reqs, 0, L, plan["chunk_blocks"])
         t1 = time.perf_counter()
         for l in range(L):
+            if plan["after"][l] > l:
+                cb.calvo_layer_event(ctx, plan["after"][l], cb.CALVO_EV_STREAM_WAIT)      # on the compute stream
             cb.calvo_prefill_attn_batch(ctx, batch, l, q[l], ks[l], vs[l], out[l], 0.0)
         t2 = time.perf_counter()
         torch.cuda.synchronize()
@@ -213,6 +239,19 @@ def main():
                 ingest_only()                      # attention needs a resident prefix
             for _ in range(args.warmup):
                 fn()
+            if args.mode == "attn" and args.gap_ms > 0:
+                kt = []
+                for _ in range(max(args.steps, 1)):
+                    for l in range(L):
+                        torch.cuda.synchronize()
+                        t_end = time.perf_counter() + args.gap_ms * 1e-3
+                        while time.perf_counter() < t_end:
+                            pass
+                        cb.calvo_prefill_attn_batch(ctx, batch, l, q[l], ks[l], vs[l], out[l], 0.0)
+                        kt.append(cb.calvo_attn_kernel_ms(ctx, l))
+                log(f"[bench] mode attn, {args.gap_ms:g} ms idle before every launch: kernel {statistics.mean(kt):.3f} ms "
+                    f"(min {min(kt):.3f} max {max(kt):.3f}) = {w.attn_flop() / L / statistics.mean(kt) / 1e9:.1f} TFLOP/s")
+                return
             t = [timed(fn) for _ in range(args.steps)]
             log(f"[bench] mode {args.mode}{' (zero data)' if args.zero_data else ''}: {statistics.mean(t):.3f} ms per pass over {L} layers"
                 + (f" = {w.attn_flop() / statistics.mean(t) / 1e9:.1f} TFLOP/s" if args.mode == "attn" else ""))
@@ -230,6 +269,8 @@ def main():
             args.tail_chunks = 4 if t_ing > t_att >= 0.5 * t_ing else 0
             head_chunks = t_att > t_ing and L > 1 and len(w.requests) == 1
         set_tail_chunks(4 if head_chunks else args.tail_chunks, head=head_chunks)
+        if not args.no_alap and t_ing > t_att:
+            set_alap(t_ing, t_att)
         # the interpreter's cyclic collector would otherwise run a full pass (tens of milliseconds with torch
         # loaded) in the middle of some step's enqueue loop
         import gc
@@ -273,6 +314,7 @@ def main():
                        "head_dim": s.head_dim, "block_tokens": s.block_tokens,
                        "prefix_tokens": [r.prefix_len for r in w.requests],
                        "suffix_tokens": [r.suffix_len for r in w.requests],
+                       "attention_waits_for_layer": plan["after"],
                        "ingest": "zero-copy kernel" if args.staging_mib == 0 else f"copy engine, {args.staging_mib} MiB staging x{args.n_staging or 2}",
                        "chunked_layers": ("first layer x 4 chunks" if head_chunks else
                                           f"last {args.tail_layers} layers x {args.tail_chunks} chunks" if args.tail_chunks else "none")},

@@ -9,7 +9,6 @@ namespace attn {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
@@ -49,6 +48,17 @@ __device__ inline float half_swap_sum(float v) {
   return a + b;
 }
 
+// maximum / sum over the four lanes c, c+16, c+32, c+48 (the lanes that share a query): every lane
+// of the wave must call these
+__device__ inline float quad_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return half_swap_max(v);
+}
+__device__ inline float quad_sum(float v) {
+  v += __shfl_xor(v, 16, 64);
+  return half_swap_sum(v);
+}
+
 // 64 lanes x 16 bytes from global memory (uniform base + per-lane byte offset) to 1 KiB of LDS
 // starting at lds_addr (uniform).  Completion is tracked by vmcnt.  No "memory" clobber on
 // purpose: every read of the deposited data sits behind wait_vm + a workgroup barrier, and a
@@ -70,9 +80,11 @@ __device__ inline void wait_vm() {
 }
 
 __device__ inline bf16x8 read_k(const lds_u8* a) { return *(const __attribute__((address_space(3))) bf16x8*)a; }
+// V^T operand of a 16x16x32 MFMA: four keys for the lane's d from the rows the 16-lane group points
+// at, and four more from 16 rows further on
 __device__ inline bf16x8 read_vt(const lds_u8* a) {
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a + 8 * kRow));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a + 16 * kRow));
   const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, both);
 }

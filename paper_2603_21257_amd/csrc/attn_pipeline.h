@@ -1,22 +1,33 @@
 // Paged causal GQA prefill attention for gfx950 (CDNA4), software-pipelined kernel body shared by
 // the 8-wave and the 4-wave workgroup shapes: bf16 storage, head_dim 128,
-// v_mfma_f32_32x32x16_bf16 for both contractions, fp32 online softmax.
+// v_mfma_f32_16x16x32_bf16 for both contractions, fp32 online softmax.
 //
-// Transposed formulation (every softmax statistic is lane-local):
+// Why the 16x16x32 shape: the part is power limited under matrix load, and on normally
+// distributed operands this shape sustains 12 % more flop/s than 32x32x16 at the power limit
+// (2010-2040 against 1800-1820 TFLOP/s with nothing but MFMAs on every SIMD: half the accumulator
+// traffic per product).  It costs issue slots (twice the instructions; on all-zero data, where
+// nothing limits the clock, the kernel is slower), and wins on real data.
+//
+// Transposed formulation (every softmax statistic stays in a lane's own registers):
 //   S^T[key][query] = K[key][:] . Q[query][:]       A = K rows from LDS, B = Q in registers
 //   O^T[d][query]  += V^T[d][key] * P^T[key][query]  A = V^T, B = P^T
-// In the 32x32 accumulator layout a lane holds one query column and 16 keys: row max / row sum
-// are reductions inside a lane plus one exchange with lane^32, the O rescale is a per-lane scalar,
-// and P^T is already the B operand of the second MFMA.  V stays token-major in LDS (as in the
-// pool); the d-major operand comes from the LDS transpose read ds_read_b64_tr_b16.
+// A wave owns 32 queries = two blocks of 16 (qb); a 32-key sub-tile is two blocks of 16 keys (kb).
+// Lane (c = lane % 16, g = lane / 16) of a 16x16 accumulator tile (kb, qb) holds query 16qb + c and
+// the keys 16kb + 4g + r, r = 0..3: a lane works on two query columns with 8 keys each, the four
+// lanes c, c+16, c+32, c+48 share a query (row max and row sum cross them only in the rare slow
+// path and at the end), the O rescale is one scalar per lane and query block, and the weights of a
+// lane are exactly the eight k-slots 8g..8g+7 of the B operand of the second MFMA when the k-slot
+// order is taken as (kb, r): slot 8g + 4kb + r <-> key 16kb + 4g + r.  V stays token-major in LDS
+// (as in the pool); the d-major A operand in that key order comes from two LDS transpose reads
+// (ds_read_b64_tr_b16: keys 4g..4g+3 and 16+4g..16+4g+3 for d = 16db + c).
 //
 // Schedule.  The key loop advances in 32-key sub-tiles.  For sub-tile j
-//     QK(j):  S_j = K_j Q^T                                     8 MFMA
+//     QK(j):  S_j = K_j Q^T                                     16 MFMA
 //     SM(j):  P_j = 2^(c (S_j - m)), row sums                   vector ALU
-//     PV(j):  O^T += V_j^T P_j^T                                8 MFMA
-// A wave runs the cycle  SM(j) -> MF(j) = {PV(j), QK(j+1)} -> SM(j+1) -> ...: the 16 MFMAs of
-// MF(j) alternate QK_k and PV_k (consecutive MFMAs never share an accumulator) and read their
-// LDS operands four MFMAs ahead.  S and P are single-buffered: S_j is dead once SM(j) has
+//     PV(j):  O^T += V_j^T P_j^T                                16 MFMA
+// A wave runs the cycle  SM(j) -> MF(j) = {PV(j), QK(j+1)} -> SM(j+1) -> ...: MF(j) reads 16 A
+// operands from LDS, alternately a K operand (16 keys x 32 d) and a V^T operand (16 d x 32 keys),
+// each used by two MFMAs (one per query block), four operands ahead of the MFMAs that consume them.  S and P are single-buffered: S_j is dead once SM(j) has
 // produced P_j, P_j is dead once MF(j) has consumed it.  The steady loop is unrolled by the ring
 // depth so that LDS ring slots are immediates.
 //
@@ -28,7 +39,7 @@
 //     waves of a SIMD belong to different workgroups and nothing couples them.  Tiles of 32 query
 //     tokens per head instead of 64: for short suffixes.
 //
-// (Measured alternatives: running QK(t+1), SM(t), PV(t-1) as one interleaved stream in every wave
+// (Measured alternatives on the 32x32x16 shape: running QK(t+1), SM(t), PV(t-1) as one interleaved stream in every wave
 // keeps the matrix pipe 96 % busy in a microbenchmark where the two waves of a SIMD run free, but
 // not behind the per-step barrier the shared K/V ring needs: the lower-numbered wave wins every
 // arbitration, finishes its step in 1180 cycles and waits 480 for the other one.  Wave priorities
@@ -53,7 +64,8 @@
 // s_waitcnt vmcnt(8) + one barrier: everything requested more than 8 instructions ago has landed.
 // Rows are unpadded; 16-byte chunks are XOR-swizzled on the way in (the lane that owns LDS chunk
 // position c fetches logical chunk c ^ f(row)) so that operand reads are bank-conflict free:
-// K f = row & 15, V f = (row & 3) << 2.  Operand addresses are lane constants plus immediates.
+// K f = row & 15 (a 16-lane group reads one chunk of 16 different rows), V f = (row & 7) << 1 (half
+// a wave reads two chunks of 8 different rows).  Operand addresses are lane constants plus immediates.
 //
 // Sub-tiles that touch the causal diagonal or the end of the context are not pipelined: they are
 // at most a handful per workgroup, are loaded synchronously and run QK -> mask -> SM -> PV.
@@ -90,8 +102,8 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int ln = lane & 31;
-  const int lh = lane >> 5;
+  const int c = lane & 15;                             // query column inside a block of 16 / row of an A operand
+  const int g = lane >> 4;                             // k-slots 8g..8g+7 of an operand, rows 4g..4g+3 of a result tile
 
   // ---- work item decode (wave-uniform)
   const int HW = p.heads_per_wg;
@@ -137,43 +149,48 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   const int Hkv = p.n_kv_heads, Hq = p.n_q_heads;
   const float c2 = p.scale * 1.4426950408889634f;
 
-  // ---- Q as the B operand of QK^T: lane (query ln, half lh) holds Q[query][16ks + 8lh .. +8]
-  bf16x8 qB[8];
+  // ---- Q as the B operand of QK^T: lane (c, g) holds Q[query 16qb + c][32ks + 8g .. +8]
+  bf16x8 qB[2][4];
   {
     const unsigned short* q = (const unsigned short*)p.q;
-    const int tokq = wq0 + ln;
-    const bool ok = tokq < S;
-    const unsigned short* row = q + ((int64_t)(rd.q_off + (ok ? tokq : 0)) * Hq + hq) * kD + 8 * lh;
 #pragma unroll
-    for (int ks = 0; ks < 8; ks++) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (ok) v = *(const u32x4*)(row + 16 * ks);
-      qB[ks] = __builtin_bit_cast(bf16x8, v);
+    for (int qb = 0; qb < 2; qb++) {
+      const int tokq = wq0 + 16 * qb + c;
+      const bool ok = tokq < S;
+      const unsigned short* row = q + ((int64_t)(rd.q_off + (ok ? tokq : 0)) * Hq + hq) * kD + 8 * g;
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (ok) v = *(const u32x4*)(row + 32 * ks);
+        qB[qb][ks] = __builtin_bit_cast(bf16x8, v);
+      }
     }
   }
 
-  f32x16 o[4];
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  f32x4 o[8][2];                                       // O^T tile (db, qb): d = 16db + 4g + r, query 16qb + c
 #pragma unroll
-  for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) o[dt][r] = 0.f;
+  for (int db = 0; db < 8; db++) {
+    o[db][0] = zero4;
+    o[db][1] = zero4;
+  }
   // Softmax state per query.  O and l_run are sums of weights 2^(x - m_run), x the exponent of a
   // score (c * score): m_run is kept in exponent units.  In the steady loop m_run
   // is a reference that is only raised when a lane's partial row sum would pass kLazyBound; it is
   // always the exact maximum of some earlier sub-tile, so the largest weight of a row is at least 1.
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};     // per query block
   // ---- pool -> LDS.  Sub-tile j = blocks 2j and 2j+1.  Wave w fetches 32 / NW rows of block
   // 2j + wblk with NI instructions of 4 rows for K and as many for V.  In instruction h lane l owns
   // row brow0 + 4h + l/16 and LDS chunk position l%16, and fetches the logical chunk that the
-  // swizzle maps there.  The second instruction's rows lie 4 rows further on: for V the swizzle
-  // (row & 3) is the same, so the same lane offsets serve with the base moved by four rows; for K the
-  // swizzle (row & 15) differs in bit 2 of the chunk index, i.e. bit 6 of the byte offset.
+  // swizzle maps there.  The second instruction's rows lie 4 rows further on: bit 2 of the row
+  // number flips, i.e. bit 2 of the chunk index for K (bit 6 of the byte offset) and bit 3 for V
+  // (bit 7 of the byte offset).
   const unsigned char* pool = (const unsigned char*)p.pool_layer;
   const int64_t half_b = (int64_t)kBlockTokens * Hkv * kD * 2;         // K half of a block, bytes
   const int brow0 = (32 / NW) * (wave % (NW / 2)) + (lane >> 4);       // row inside the block, first instruction
   const unsigned rowoff = (unsigned)(brow0 * Hkv * kD * 2 + kv * kD * 2);
   const unsigned voff_k = rowoff + (((lane & 15) ^ (brow0 & 15)) << 4);
-  const unsigned voff_v = rowoff + (((lane & 15) ^ ((brow0 & 3) << 2)) << 4);
+  const unsigned voff_v = rowoff + (((lane & 15) ^ ((brow0 & 7) << 1)) << 4);
   const int64_t rows4 = (int64_t)4 * Hkv * kD * 2;
   const unsigned dma_lds = lds0 + wave * (1024 * NI);                  // + h*1024 + slot*8192 (+ V ring)
 
@@ -185,7 +202,7 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   };
   auto request_v_at = [&](int64_t off, int slot) {
     dma_1k(pool + half_b + off, voff_v, dma_lds + kVBase + slot * kSlot);
-    if constexpr (NI == 2) dma_1k(pool + half_b + off + rows4, voff_v, dma_lds + kVBase + slot * kSlot + 1024);
+    if constexpr (NI == 2) dma_1k(pool + half_b + off + rows4, voff_v ^ 128u, dma_lds + kVBase + slot * kSlot + 1024);
   };
   auto request_k = [&](int j) { request_k_at(fetch_off(j), j & RM); };
   auto request_v = [&](int j) { request_v_at(fetch_off(j), j & RM); };
@@ -199,7 +216,7 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
       const unsigned l_k = dma_lds + (j & RM) * kSlot + h * 1024;
       if (live) {
         dma_1k(pool + boff + h * rows4, h ? voff_k ^ 64u : voff_k, l_k);
-        dma_1k(pool + boff + half_b + h * rows4, voff_v, l_k + kVBase);
+        dma_1k(pool + boff + half_b + h * rows4, h ? voff_v ^ 128u : voff_v, l_k + kVBase);
       } else {
         *(u32x4*)(smem + (l_k - lds0) + kVBase + (lane << 4)) = (u32x4){0u, 0u, 0u, 0u};
       }
@@ -207,19 +224,19 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   };
 
   // ---- lane-constant operand addresses inside a slot
-  // K operand: row ln, logical chunk 2ks+lh
-  const lds_u8* ka_addr[8];
+  // K operand (kb, ks): key row 16kb + c, logical chunk 4ks + g (d = 32ks + 8g .. +8); the key block
+  // adds 16 rows, which leaves the swizzle alone
+  const lds_u8* ka_addr[4];
 #pragma unroll
-  for (int ks = 0; ks < 8; ks++) ka_addr[ks] = lds + ln * kRow + (((2 * ks + lh) ^ (ln & 15)) << 4);
-  // V^T operand: 16-lane group g16 covers d = 16*(g16&1)..+16 of a 32-wide d tile and 4 tokens
-  // starting at 4*(g16>>1); source lane s16 points at token s16/4, d offset 4*(s16%4)
-  const int g16 = lane >> 4, s16 = lane & 15;
-  const int v_row = 4 * (g16 >> 1) + (s16 >> 2);
-  const int v_c0 = 2 * (g16 & 1) + ((s16 & 3) >> 1);
-  const lds_u8* va_addr[4];
+  for (int ks = 0; ks < 4; ks++) ka_addr[ks] = lds + c * kRow + (((4 * ks + g) ^ c) << 4);
+  // V^T operand db: the 16 lanes of group g read keys 4g..4g+3 (and, 16 rows further, 16+4g..) for
+  // d = 16db..16db+15: source lane c points at key 4g + c/4, d offset 16db + 4*(c%4); after the
+  // transpose lane c holds the four keys for d = 16db + c
+  const int v_row = 4 * g + (c >> 2);
+  const lds_u8* va_addr[8];
 #pragma unroll
-  for (int dt = 0; dt < 4; dt++)
-    va_addr[dt] = lds + kVBase + v_row * kRow + ((4 * (dt ^ (v_row & 3)) + v_c0) << 4) + (s16 & 1) * 8;
+  for (int db = 0; db < 8; db++)
+    va_addr[db] = lds + kVBase + v_row * kRow + ((2 * (db ^ (v_row & 7)) + ((c & 3) >> 1)) << 4) + (c & 1) * 8;
 
   // two weights rounded to bf16 (nearest even), packed
   auto pack_bf16 = [](float a, float b) -> unsigned {
@@ -230,68 +247,77 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   };
 
   // ---- pipeline registers: S and P of the sub-tile in flight
-  f32x16 sbuf;
+  // S tile (kb, qb): keys 16kb + 4g + r of query 16qb + c.  P operand of query block qb: the lane's
+  // eight weights in k-slot order (kb, r).
+  struct STile { f32x4 t[2][2]; };
+  STile sbuf;
   bf16x8 pbuf[2];
-  // Rescale of O that a raised reference asks for before the next PV: al per lane, needed for the
-  // wave (a scalar: the steady path spends no vector instruction on it).
-  float al = 1.f;
+  // Rescale of O that a raised reference asks for before the next PV: al per lane and query block,
+  // needed for the wave (a scalar: the steady path spends no vector instruction on it).
+  float al[2] = {1.f, 1.f};
   bool needed = false;
 
-  auto rescale = [&](float a) {
+  auto rescale = [&](const float (&a)[2]) {
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) o[dt][r] *= a;
+    for (int db = 0; db < 8; db++) {
+      o[db][0] *= a[0];
+      o[db][1] *= a[1];
+    }
   };
-  // exponent of score s against the current reference
-  auto expo = [&](float s) -> float { return __builtin_fmaf(s, c2, -m_run); };
-  auto qk = [&](int slot, f32x16& s) {
-    bf16x8 ka[8];
+  // exponent of score s of query block qb against the current reference
+  auto expo = [&](float s, int qb) -> float { return __builtin_fmaf(s, c2, -m_run[qb]); };
+  auto qk = [&](int slot, STile& s) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ks++) ka[ks] = read_k(ka_addr[ks] + slot * kSlot);
-    f32x16 z;
+    for (int kb = 0; kb < 2; kb++) {
+      bf16x8 ka[4];
 #pragma unroll
-    for (int r = 0; r < 16; r++) z[r] = 0.f;
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qB[0], z, 0, 0, 0);
+      for (int ks = 0; ks < 4; ks++) ka[ks] = read_k(ka_addr[ks] + 16 * kb * kRow + slot * kSlot);
 #pragma unroll
-    for (int ks = 1; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qB[ks], s, 0, 0, 0);
+      for (int qb = 0; qb < 2; qb++) {
+        f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0], qB[qb][0], zero4, 0, 0, 0);
+#pragma unroll
+        for (int ks = 1; ks < 4; ks++) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qB[qb][ks], acc, 0, 0, 0);
+        s.t[kb][qb] = acc;
+      }
+    }
   };
-  auto row_max = [&](const f32x16& s) -> float {
-    float mx = fmaxf(s[0], s[1]);
+  // largest score of the lane's query of block qb over the whole sub-tile (all four lanes of the query)
+  auto row_max = [&](const STile& s, int qb) -> float {
+    float mx = fmaxf(fmaxf(s.t[0][qb][0], s.t[0][qb][1]), fmaxf(s.t[0][qb][2], s.t[0][qb][3]));
+    mx = fmaxf(mx, fmaxf(fmaxf(s.t[1][qb][0], s.t[1][qb][1]), fmaxf(s.t[1][qb][2], s.t[1][qb][3])));
+    return quad_max(mx);
+  };
+  // weights of query block qb against the current reference: fp32 sum, bf16 operand
+  auto weights_of = [&](const STile& s, int qb, float& ps, bf16x8& pb) {
+    float w[8];
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-    return half_swap_max(mx);
+    for (int e = 0; e < 8; e++) w[e] = __builtin_amdgcn_exp2f(expo(s.t[e >> 2][qb][e & 3], qb));
+    ps = ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+    pb = __builtin_bit_cast(bf16x8, (u32x4){pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3]), pack_bf16(w[4], w[5]), pack_bf16(w[6], w[7])});
   };
   // Textbook update for one sub-tile whose scores are in s (possibly masked with -inf): new
   // running maximum, rescale factor alpha for l and O, weights against the new maximum (summed in
   // fp32, rounded to bf16 once for the PV product).
-  auto sm_textbook = [&](const f32x16& s, bf16x8 (&pb)[2], float& alpha, bool& changed) {
-    const float m_new = fmaxf(m_run, row_max(s) * c2);
-    alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    changed = (m_new != m_run);
-    m_run = m_new;
-    float ps0 = 0.f, ps1 = 0.f;
-    unsigned pk[8];
+  auto sm_textbook = [&](const STile& s, bf16x8 (&pb)[2], float (&alpha)[2], bool& changed) {
+    changed = false;
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      const float w0 = __builtin_amdgcn_exp2f(expo(s[2 * e]));
-      const float w1 = __builtin_amdgcn_exp2f(expo(s[2 * e + 1]));
-      ps0 += w0;
-      ps1 += w1;
-      pk[e] = pack_bf16(w0, w1);
+    for (int qb = 0; qb < 2; qb++) {
+      const float m_new = fmaxf(m_run[qb], row_max(s, qb) * c2);
+      alpha[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+      changed |= (m_new != m_run[qb]);
+      m_run[qb] = m_new;
+      float ps;
+      weights_of(s, qb, ps, pb[qb]);
+      l_run[qb] = l_run[qb] * alpha[qb] + ps;
     }
-    l_run = l_run * alpha + (ps0 + ps1);
-    pb[0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
-    pb[1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
   };
   auto pv = [&](int slot, const bf16x8 (&pb)[2]) {
 #pragma unroll
-    for (int jj = 0; jj < 2; jj++)
-#pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        const bf16x8 a = read_vt(va_addr[dt] + slot * kSlot + 16 * jj * kRow);
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[jj], o[dt], 0, 0, 0);
-      }
+    for (int db = 0; db < 8; db++) {
+      const bf16x8 a = read_vt(va_addr[db] + slot * kSlot);
+      o[db][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[0], o[db][0], 0, 0, 0);
+      o[db][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[1], o[db][1], 0, 0, 0);
+    }
   };
 
   // Block offsets for the requests of one unrolled iteration (steps t0 .. t0+RING-1, t0 & RM == 1):
@@ -300,12 +326,13 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   int64_t off_cur[RING], off_prev1 = 0, off_prev2 = 0;
   // first kPD MFMA operands of the coming MFMA half (see step_steady)
   bf16x8 pre[kPD];
-  // operand i of MF(j): K chunk i/2 of K(j+1) (i even) or V^T chunk i/2 of V(j) (i odd)
+  // operand i of MF(j), k = i % 8: the K operand (key block k%2, d slice k/2) of K(j+1) for i < 8, the
+  // V^T operand of d block k of V(j) for i >= 8
   auto load_opnd = [&](auto idx, auto ks, auto vs) -> bf16x8 {
-    constexpr int i = decltype(idx)::value, k = i >> 1;
+    constexpr int i = decltype(idx)::value, k = i & 7;
     constexpr int KS = decltype(ks)::value, VS = decltype(vs)::value;
-    if constexpr (i & 1) return read_vt(va_addr[k & 3] + VS * kSlot + 16 * (k >> 2) * kRow);
-    else return read_k(ka_addr[k] + KS * kSlot);
+    if constexpr (i >= 8) return read_vt(va_addr[k] + VS * kSlot);
+    else return read_k(ka_addr[k >> 1] + 16 * (k & 1) * kRow + KS * kSlot);
   };
   auto prefetch = [&](auto ks, auto vs) {
     static_for<0, kPD>([&](auto idx) { pre[decltype(idx)::value] = load_opnd(idx, ks, vs); });
@@ -329,80 +356,78 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
     // Softmax of the sub-tile in sbuf -> pbuf.  The empty asm statements tie the inputs and results
     // of each half to its side: the compiler may not move them across.
     auto valu_half = [&]() {
-      pin(m_run);
-      const f32x16& s = sbuf;
+      pin(m_run[0]);
+      pin(m_run[1]);
+      const STile& s = sbuf;
       bool raised = false;
-      float ps;
-      unsigned pk[8];
-      // weights of accumulator registers 2e, 2e+1: summed in fp32 (two chains), then rounded to
-      // bf16 once for the PV product
-      auto weights = [&]() {
-        float ps0 = 0.f, ps1 = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-          const float w0 = __builtin_amdgcn_exp2f(expo(s[2 * e]));
-          const float w1 = __builtin_amdgcn_exp2f(expo(s[2 * e + 1]));
-          ps0 += w0;
-          ps1 += w1;
-          pk[e] = pack_bf16(w0, w1);
-        }
-        ps = ps0 + ps1;
-      };
-      weights();
+      float ps[2];
+      weights_of(s, 0, ps[0], pbuf[0]);
+      weights_of(s, 1, ps[1], pbuf[1]);
       // Accept unless a partial row sum is above the bound (or not a number).  Otherwise raise the
-      // reference to this sub-tile's maximum, rescale the running sum (O is rescaled at the start
+      // references to this sub-tile's maxima, rescale the running sums (O is rescaled at the start
       // of the next MFMA half through al / needed) and compute the weights again: now all are <= 1.
-      if (__builtin_amdgcn_ballot_w64(!(ps <= kLazyBound)) != 0) {
-        // this sub-tile's maximum, as an exponent relative to the current reference
-        const float d = fmaxf(expo(row_max(s)), 0.f);
-        const float a_acc = __builtin_amdgcn_exp2f(-d);
-        raised = __builtin_amdgcn_ballot_w64(d > 0.f) != 0;
-        l_run *= a_acc;
-        al = a_acc;
-        m_run += d;
-        weights();
+      if (__builtin_amdgcn_ballot_w64(!(ps[0] <= kLazyBound) || !(ps[1] <= kLazyBound)) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; qb++) {
+          // this sub-tile's maximum, as an exponent relative to the current reference
+          const float d = fmaxf(expo(row_max(s, qb), qb), 0.f);
+          const float a_acc = __builtin_amdgcn_exp2f(-d);
+          raised |= __builtin_amdgcn_ballot_w64(d > 0.f) != 0;
+          l_run[qb] *= a_acc;
+          al[qb] = a_acc;
+          m_run[qb] += d;
+          weights_of(s, qb, ps[qb], pbuf[qb]);
+        }
       }
-      l_run += ps;
-      pbuf[0] = __builtin_bit_cast(bf16x8, (u32x4){pk[0], pk[1], pk[2], pk[3]});
-      pbuf[1] = __builtin_bit_cast(bf16x8, (u32x4){pk[4], pk[5], pk[6], pk[7]});
+      l_run[0] += ps[0];
+      l_run[1] += ps[1];
       needed = raised;
       pin(pbuf[0]);
       pin(pbuf[1]);
-      pin(l_run);
+      pin(l_run[0]);
+      pin(l_run[1]);
     };
-    // The 16 MFMAs alternate QK_k and PV_k; operand i is read from LDS kPD operands ahead of the
-    // MFMA that consumes it.  The first kPD operands (pre[]) are read by prefetch() well before
-    // the MFMA half starts, so no LDS latency is exposed.
+    // Eight K operands, then eight V^T operands, two MFMAs each (query blocks 0 and 1): all of QK(t+1)
+    // before all of PV(t).  Keeping the MFMAs of one contraction together is worth 2 % over alternating
+    // them (measured; the B operands then change between Q and P once per step, not every instruction,
+    // and the part is power limited).  Operand i is read from LDS kPD operands ahead of the MFMAs that
+    // consume it; the first kPD operands (pre[]) are read by prefetch() well before the MFMA half
+    // starts, so no LDS latency is exposed.
     bf16x8 opnd[16];
     auto mfma_half = [&]() {
-      pin(qB[0]);
+      pin(qB[0][0]);
       pin(pbuf[0]);
       pin(pbuf[1]);
       if (needed) rescale(al);
-      f32x16 sn;
+      STile sn;
       static_for<0, kPD>([&](auto idx) { opnd[decltype(idx)::value] = pre[decltype(idx)::value]; });
       static_for<0, 16>([&](auto idx) {
-        constexpr int i = decltype(idx)::value, k = i >> 1;
-        if constexpr (i & 1) {
-          o[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], pbuf[k >> 2], o[k & 3], 0, 0, 0);
-        } else if constexpr (k == 0) {
-          f32x16 z;
-#pragma unroll
-          for (int r = 0; r < 16; r++) z[r] = 0.f;
-          sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], qB[0], z, 0, 0, 0);
+        constexpr int i = decltype(idx)::value, k = i & 7;
+        if constexpr (i >= 8) {
+          o[k][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], pbuf[0], o[k][0], 0, 0, 0);
+          o[k][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], pbuf[1], o[k][1], 0, 0, 0);
         } else {
-          sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i], qB[k], sn, 0, 0, 0);
+          constexpr int kb = k & 1, ks = k >> 1;
+          sn.t[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], qB[0][ks], ks == 0 ? zero4 : sn.t[kb][0], 0, 0, 0);
+          sn.t[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(opnd[i], qB[1][ks], ks == 0 ? zero4 : sn.t[kb][1], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         if constexpr (i + kPD < 16) {
           opnd[i + kPD] = load_opnd(Tag<i + kPD>{}, Tag<KS>{}, Tag<VS>{});
-          __builtin_amdgcn_sched_group_barrier(0x100, ((i + kPD) & 1) ? 2 : 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, (i + kPD >= 8) ? 2 : 1, 0);
         }
       });
       sbuf = sn;
-      pin(sbuf);
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) pin(o[dt]);
+      for (int kb = 0; kb < 2; kb++) {
+        pin(sbuf.t[kb][0]);
+        pin(sbuf.t[kb][1]);
+      }
+#pragma unroll
+      for (int db = 0; db < 8; db++) {
+        pin(o[db][0]);
+        pin(o[db][1]);
+      }
     };
     if (!ahead) {
       requests();
@@ -506,18 +531,19 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
     __syncthreads();
     const int k0 = (jb + j) * kSK;
     if (wave_active && k0 <= pq_max) {
-      f32x16 s;
+      STile s;
       qk(j & RM, s);
       if (k0 + 31 > pq_min) {
-        const int pq = pq_min + ln;
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int kt = k0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          if (kt > pq) s[r] = -INFINITY;
-        }
+        for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+          for (int qb = 0; qb < 2; qb++)
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+              if (k0 + 16 * kb + 4 * g + r > pq_min + 16 * qb + c) s.t[kb][qb][r] = -INFINITY;
       }
       bf16x8 pb[2];
-      float alpha;
+      float alpha[2];
       bool changed;
       sm_textbook(s, pb, alpha, changed);
       if (__builtin_amdgcn_ballot_w64(changed) != 0) rescale(alpha);
@@ -527,46 +553,50 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
   }
 
   // ---- one piece of a split tile: leave the unnormalised O, the reference (exponent units) and
-  // the row sum for merge_splits_kernel.  Lane holds d = 32dt + 8(r/4) + 4lh + r%4 of query row ln.
+  // the row sum for merge_splits_kernel (32 rows x 128 floats per wave, row = 16qb + c).  Lane holds
+  // d = 16db + 4g + r of the query rows 16qb + c.
   if (wi.n_splits > 1) {
-    if (wave_active && wq0 + ln < S) {
+    if (wave_active) {                       // wave-uniform: every lane takes part in the exchanges
       const int64_t slot = ((int64_t)it * NHG + hg) * NW + wave;
-      float* po = p.part_o + (slot * 32 + ln) * kD + 4 * lh;
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++)
+      for (int qb = 0; qb < 2; qb++) {
+        const float lt = quad_sum(l_run[qb]);
+        if (wq0 + 16 * qb + c < S) {
+          float* po = p.part_o + (slot * 32 + 16 * qb + c) * kD + 4 * g;
 #pragma unroll
-        for (int rq = 0; rq < 4; rq++)
-          *(f32x4*)(po + 32 * dt + 8 * rq) = (f32x4){o[dt][4 * rq], o[dt][4 * rq + 1], o[dt][4 * rq + 2], o[dt][4 * rq + 3]};
-      const float lt = half_swap_sum(l_run);
-      if (lh == 0) {
-        float* pm = p.part_ml + (slot * 32 + ln) * 2;
-        pm[0] = m_run;
-        pm[1] = lt;
+          for (int db = 0; db < 8; db++) *(f32x4*)(po + 16 * db) = o[db][qb];
+          if (g == 0) {
+            float* pm = p.part_ml + (slot * 32 + 16 * qb + c) * 2;
+            pm[0] = m_run[qb];
+            pm[1] = lt;
+          }
+        }
       }
     }
     return;
   }
 
-  // ---- normalise and write O[token][head][d]; lane holds d = 32dt + 8(r/4) + 4lh + r%4
+  // ---- normalise and write O[token][head][d]; lane holds d = 16db + 4g + r of the rows 16qb + c
   if (wave_active) {
     unsigned short* out = (unsigned short*)p.out;
-    const float lt = half_swap_sum(l_run);
-    const float inv = 1.f / lt;
-    const int tokq = wq0 + ln;
-    if (tokq < S) {
-      unsigned short* row = out + ((int64_t)(rd.q_off + tokq) * Hq + hq) * kD + 4 * lh;
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++)
+    for (int qb = 0; qb < 2; qb++) {
+      const float lt = quad_sum(l_run[qb]);
+      const float inv = 1.f / lt;
+      const int tokq = wq0 + 16 * qb + c;
+      if (tokq < S) {
+        unsigned short* row = out + ((int64_t)(rd.q_off + tokq) * Hq + hq) * kD + 4 * g;
 #pragma unroll
-        for (int rq = 0; rq < 4; rq++) {
+        for (int db = 0; db < 8; db++) {
           bf16x2 a, b;
-          a[0] = (__bf16)(o[dt][4 * rq + 0] * inv);
-          a[1] = (__bf16)(o[dt][4 * rq + 1] * inv);
-          b[0] = (__bf16)(o[dt][4 * rq + 2] * inv);
-          b[1] = (__bf16)(o[dt][4 * rq + 3] * inv);
+          a[0] = (__bf16)(o[db][qb][0] * inv);
+          a[1] = (__bf16)(o[db][qb][1] * inv);
+          b[0] = (__bf16)(o[db][qb][2] * inv);
+          b[1] = (__bf16)(o[db][qb][3] * inv);
           u32x2 w = {__builtin_bit_cast(unsigned int, a), __builtin_bit_cast(unsigned int, b)};
-          *(u32x2*)(row + 32 * dt + 8 * rq) = w;
+          *(u32x2*)(row + 16 * db) = w;
         }
+      }
     }
   }
 }
