@@ -84,9 +84,9 @@ def main():
                     help="diagnostic, with --mode attn: the GPU idles this long before every attention launch (the clock "
                          "has to ramp up again after an idle gap; the kernel time is reported)")
     ap.add_argument("--no-alap", action="store_true",
-                    help="queue every layer's attention behind its own layer's loading signal (default when attention "
-                         "bounds the step).  Default for load-bound steps: the attention chain starts as late as it can "
-                         "and still end with the last layer, so that its launches run back to back")
+                    help="queue every layer's attention behind its own layer's loading signal.  Default for load-bound "
+                         "steps with large layers whose tail is loaded in chunks: the whole-layer attention launches are "
+                         "queued so that they run back to back and reach the chunked tail when it lands")
     ap.add_argument("--leg", action="store_true", help="(internal) run as the appended leg: timing of the step only")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -269,7 +269,10 @@ def main():
             args.tail_chunks = 4 if t_ing > t_att >= 0.5 * t_ing else 0
             head_chunks = t_att > t_ing and L > 1 and len(w.requests) == 1
         set_tail_chunks(4 if head_chunks else args.tail_chunks, head=head_chunks)
-        if not args.no_alap and t_ing > t_att:
+        # Only where it pays and cannot hurt: attention a sizeable part of the loading time (the same condition as
+        # the chunked tail, which the chain ends at), and every layer a transfer of its own (small layers share
+        # transfers, and a layer's signal then fires with its group's).
+        if not args.no_alap and args.tail_chunks > 0 and not head_chunks and w.ingest_bytes() / L >= (128 << 20):
             set_alap(t_ing, t_att)
         # the interpreter's cyclic collector would otherwise run a full pass (tens of milliseconds with torch
         # loaded) in the middle of some step's enqueue loop
@@ -357,17 +360,19 @@ def main():
 
 
 def measured_mfma_peak(cb, torch, dev):
-    """calvo_mfma_peak with normally distributed and with all-zero bf16 operands."""
+    """calvo_mfma_peak with normally distributed and with all-zero bf16 operands, for the MFMA shape the attention
+    kernels use (16x16x32) and, for comparison, the 32x32x16 shape."""
     sink = torch.empty(512 * 1024, dtype=torch.float32, device=dev)
     out = {}
     for name, fill in (("normal_operands", lambda t: t.normal_(0.0, 1.0)), ("zero_operands", lambda t: t.zero_())):
         ops = torch.empty(8192, dtype=torch.bfloat16, device=dev)
         fill(ops)
         torch.cuda.synchronize()
-        tf, ms = cb.calvo_mfma_peak(ops, sink, iters=20000, repeats=3)
-        out[name] = round(tf, 1)
-        log(f"[bench] MFMA-only peak, {name}: {tf:.0f} TFLOP/s ({ms:.2f} ms per launch)")
-    out["kernel"] = "v_mfma_f32_32x32x16_bf16 only, two waves per SIMD, register operands"
+        for shape, key in ((cb.CALVO_MFMA_16x16x32, name), (cb.CALVO_MFMA_32x32x16, name + "_32x32x16")):
+            tf, ms = cb.calvo_mfma_peak(ops, sink, iters=20000, repeats=3, shape=shape)
+            out[key] = round(tf, 1)
+            log(f"[bench] MFMA-only peak, {key}: {tf:.0f} TFLOP/s ({ms:.2f} ms per launch)")
+    out["kernel"] = "v_mfma_f32_16x16x32_bf16 only (the attention kernels' shape), two waves per SIMD, register operands"
     return out
 
 

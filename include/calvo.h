@@ -524,14 +524,17 @@ int calvo_attn_plan_items(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, 
 int calvo_attn_kernel_info(calvo_ctx* ctx, int layer, int* kernel, int* n_workgroups);
 
 /* Measurement helper: the rate the matrix pipes of the current device sustain on bf16 MFMAs alone
- * (v_mfma_f32_32x32x16_bf16, two waves per SIMD on every CU, operands in registers), for the operand
- * data the caller supplies: operands = DEVICE, 16 KiB of bf16 values (the first 8 KiB feed the A
- * operands, the rest the B operands); sink = DEVICE, at least 512 * 4 bytes per compute unit, receives
- * the accumulators.  Runs on the default stream: one warm-up launch, then `repeats` launches of `iters`
- * x 16 MFMAs per wave; *tflops = the fastest of them, *ms (may be NULL) its duration.  The published
- * peak assumes the top clock; the sustained rate depends on how much the operand bits toggle.
- * CALVO_EINVAL for bad arguments, CALVO_EHIP if HIP refuses. */
-int calvo_mfma_peak(const void* operands, void* sink, int iters, int repeats, double* tflops, double* ms);
+ * (shape = CALVO_MFMA_16x16x32, the shape of the attention kernels, or CALVO_MFMA_32x32x16; two waves
+ * per SIMD on every CU, operands in registers), for the operand data the caller supplies: operands =
+ * DEVICE, 16 KiB of bf16 values (the first 8 KiB feed the A operands, the rest the B operands); sink =
+ * DEVICE, at least 512 * 4 bytes per compute unit, receives the accumulators.  Runs on the default
+ * stream: one warm-up launch, then `repeats` launches of `iters` x 16 (32x32x16) or `iters` x 32
+ * (16x16x32) MFMAs per wave - the same number of products; *tflops = the fastest of them, *ms (may be
+ * NULL) its duration.  The published peak assumes the top clock; the sustained rate depends on how
+ * much the operand bits toggle and on the shape.  CALVO_EINVAL for bad arguments, CALVO_EHIP if HIP
+ * refuses. */
+enum { CALVO_MFMA_16x16x32 = 0, CALVO_MFMA_32x32x16 = 1 };
+int calvo_mfma_peak(const void* operands, void* sink, int iters, int repeats, int shape, double* tflops, double* ms);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* calvo_last_error(void);

@@ -123,7 +123,7 @@ def lib() -> C.CDLL:
         L.calvo_batch_destroy.argtypes = [C.c_void_p]
         L.calvo_prefill_attn_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_float]
-        L.calvo_mfma_peak.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.calvo_mfma_peak.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.calvo_attn_kernel_ms.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
         L.calvo_attn_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                       C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -296,10 +296,13 @@ def calvo_prefill_attn_batch(ctx: int, batch: int, layer: int, q, k_suffix, v_su
     _check(lib().calvo_prefill_attn_batch(ctx, batch, layer, _ptr(q), _ptr(k_suffix), _ptr(v_suffix), _ptr(out), float(scale)))
 
 
-def calvo_mfma_peak(operands, sink, iters: int = 20000, repeats: int = 3):
-    """(TFLOP/s, ms) the matrix pipes sustain on bf16 MFMAs alone with the given operand data (device buffers)."""
+CALVO_MFMA_16x16x32, CALVO_MFMA_32x32x16 = 0, 1
+
+
+def calvo_mfma_peak(operands, sink, iters: int = 20000, repeats: int = 3, shape: int = CALVO_MFMA_16x16x32):
+    """(TFLOP/s, ms) the matrix pipes sustain on bf16 MFMAs of one shape alone with the given operand data (device buffers)."""
     tf, ms = C.c_double(), C.c_double()
-    _check(lib().calvo_mfma_peak(_ptr(operands), _ptr(sink), int(iters), int(repeats), C.byref(tf), C.byref(ms)))
+    _check(lib().calvo_mfma_peak(_ptr(operands), _ptr(sink), int(iters), int(repeats), int(shape), C.byref(tf), C.byref(ms)))
     return tf.value, ms.value
 
 
