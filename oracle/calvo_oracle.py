@@ -13,12 +13,12 @@ kv_ingest       The L2->L1 loading stage of the paper (Section 3.1: a block is
                 host staging area to the pool slot its block table names.  The
                 result has a plain definition (a permutation of 64-KiB byte
                 strings), so the oracle is that definition.
-suffix_append   The prefill step "constructs the KVCache" (Section 2.1): the
+suffix_append   The prefill step builds the KVCache of the prompt (Section 2.1): the
                 K/V of the tokens that are computed, not loaded, are written
                 to the request's remaining slots.  Plain definition again.
 prefill_attn    Causal attention of the query (suffix) tokens over the reused
-                prefix plus the suffix itself (Section 2.1 prefill; Section 2.1
-                "prefix caching": cached KV is reused as it is).  The paper
+                prefix plus the suffix itself (Section 2.1 prefill; Section 2.1 on
+                prefix caching: cached KV is reused as it is).  The paper
                 inherits this operation from its serving engine and prints no
                 formula; the textbook definition is used: for row i at absolute
                 position p = P + i and query head h,

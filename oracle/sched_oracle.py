@@ -82,7 +82,7 @@ def pick(policy, model, jobs, done, now):
 
 def simulate_staged(policy, model, jobs, load_s=None, comp_s=None):
     """Replay with loading and computation as two stages that each serve their highest-priority ready
-    request (Section 3.1: a stage's dispatcher works on "the highest-priority request" whose lower-level
+    request (Section 3.1: a stage's dispatcher works on the request of highest priority whose lower-level
     blocks are ready): the loading stage picks among the requests that have arrived, the compute
     stage among those whose loading has finished.  Both are non-preemptive.  Decisions are taken in
     time order; when both stages could decide at the same instant, the compute stage goes first."""
