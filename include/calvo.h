@@ -495,7 +495,7 @@ int calvo_ingest_plan(const calvo_request* reqs, int32_t n_reqs, int32_t layer_b
  * *tile_tokens = suffix tokens per work item, *pieces = split-KV pieces a tile's context is cut into at
  * most (1 = no cut; pieces are never shorter than 48 sub-tiles of 32 keys), *n_workgroups of the
  * launch.  The choice replays the launch on the device's workgroup slots and cuts tiles when that
- * shortens it: too few tiles for the chip (the paper's "long context, short query" requests), or a
+ * shortens it: too few tiles for the chip (the paper's requests: long contexts with short queries), or a
  * workgroup count just above a whole number of rounds.  CALVO_EINVAL for bad arguments. */
 int calvo_attn_plan(int32_t n_q_heads, int32_t n_kv_heads, int32_t n_cus, const int32_t* prefix_blocks,
                     const int32_t* suffix_lens, int32_t n_reqs, int32_t* kernel, int32_t* tile_tokens,

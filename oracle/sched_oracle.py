@@ -14,7 +14,7 @@ Readings taken where the paper is silent: service is non-preemptive; the schedul
 whenever the server (its loading stage, when loading and computation are pipelined as in
 Section 3.1) becomes free, among the requests that have arrived by then; if none has, it
 idles until the next arrival; ties go to the earlier arrival, then to the lower index; the
-"prefill token number" of SJF-PT is the number of tokens that are computed (the query
+token count that SJF-PT orders by is the number of tokens that are computed (the query
 tokens); a component with zero tokens costs nothing (no fixed term).
 
 Pins (tests/test_oracle_sched.py): the two-request example the paper works out in Section
