@@ -44,6 +44,23 @@ def profiled_traffic(config: int):
     return None
 
 
+def alap_schedule(n_layers: int, n_chain: int, rho: float):
+    """Which layer's loading signal each layer's attention launch waits for, so that the launches of layers
+    0 .. n_chain-1 run back to back and the last of them starts when its own blocks land (layers from n_chain on
+    wait for themselves).
+
+    Load-bound step: a layer's attention is shorter than a layer's load (rho = t_att / t_load per layer < 1), so
+    launches that each wait for their own layer run with idle gaps between them, and after every gap the clock has
+    to ramp up again (measured: --mode attn --gap-ms).  The compute chain loses nothing by starting later.  Layer j
+    lands at (j + 1) t_load and the chain has to be at layer l by n t_load - (n - 1 - l) t_att, so layer l waits for
+    layer j = n - 1 - ceil((n - 1 - l) rho), never an earlier one than itself.  The caller takes rho a few percent
+    high: the first launches after the idle start are slow."""
+    import math
+    rho = min(1.0, max(0.0, rho))
+    n = min(n_chain, n_layers)
+    return [max(l, n - 1 - math.ceil((n - 1 - l) * rho)) if l < n else l for l in range(n_layers)]
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -186,19 +203,9 @@ def main():
     plan["after"] = list(range(L))
 
     def set_alap(t_ing_ms, t_att_ms):
-        """Load-bound step: a layer's attention is shorter than a layer's load, so launches that each wait for their
-        own layer run with idle gaps between them, and after every gap the clock has to ramp up again (measured:
-        --mode attn --gap-ms).  The compute chain loses nothing by starting later: the whole-layer launches are
-        queued so that they run back to back and reach the last of them when its blocks land.  With n such layers
-        (the layers before the chunk-granular tail, which keeps following its own chunks), layer j lands at
-        (j + 1) t_load and the chain has to be at l by n t_load - (n - 1 - l) t_att, so layer l waits for layer
-        j = n - 1 - ceil((n - 1 - l) rho), rho = t_att / t_load per layer, taken 6 % high (the first launches
-        after the idle start are slow)."""
-        import math
-        rho = min(1.0, 1.06 * t_att_ms / max(t_ing_ms, 1e-9))
         cbs = plan["chunk_blocks"] or [0] * L
         n = next((l for l in range(L) if cbs[l]), L)
-        plan["after"] = [max(l, n - 1 - math.ceil((n - 1 - l) * rho)) if l < n else l for l in range(L)]
+        plan["after"] = alap_schedule(L, n, 1.06 * t_att_ms / max(t_ing_ms, 1e-9))
 
     def step():
         t0 = time.perf_counter()

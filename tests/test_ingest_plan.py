@@ -119,3 +119,24 @@ def test_layer_subrange_and_argument_checks():
         cb.calvo_ingest_plan([req(BASE, nb * BLK, nb)], 0, 2, BLK, 64, chunk_blocks=[3, 0])
     g, runs = cb.calvo_ingest_plan([], 0, 3, BLK, 64)
     assert list(runs) == [0, 0, 0]
+
+
+def test_back_to_back_attention_chain_schedule():
+    """bench.alap_schedule: every launch waits for its own layer or a later one, in non-decreasing order; the chain
+    is feasible (the awaited layer lands no later than a back-to-back chain ending with the last chain layer would
+    reach the launch), as late as a whole layer allows, and rho >= 1 degenerates to one launch per landed layer."""
+    import math
+    import bench
+    for L, n, rho in [(32, 26, 0.78), (32, 32, 0.45), (48, 42, 0.93), (8, 8, 0.0), (5, 3, 0.5), (4, 0, 0.7)]:
+        after = bench.alap_schedule(L, n, rho)
+        assert len(after) == L and all(a >= l for l, a in enumerate(after)) and after == sorted(after)
+        assert after[n:] == list(range(n, L))
+        for l in range(min(n, L)):
+            lands = after[l] + 1                                   # in units of one layer's load
+            due = n - (n - 1 - l) * rho                            # when the chain has to start launch l
+            assert lands <= due + 1e-9 or after[l] == l
+            assert after[l] == l or lands + 1 > due - 1e-9         # not a whole layer earlier than needed
+        if n:
+            assert after[n - 1] == n - 1
+    assert bench.alap_schedule(6, 6, 1.0) == list(range(6)) and bench.alap_schedule(6, 6, 1.7) == list(range(6))
+    assert bench.alap_schedule(6, 6, 0.0) == [5] * 6
