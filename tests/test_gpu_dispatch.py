@@ -263,6 +263,36 @@ def test_degenerate_jobs_pass_through_every_stage(three_stage):
         assert r["submit_s"] <= r["load_start_s"] <= r["load_end_s"] <= r["first_token_s"]
 
 
+def test_submit_refuses_layer_strides_that_leave_the_allocation():
+    """q, k/v and out with their layer strides must lie inside one device allocation each: a stride meant for a
+    larger buffer is refused on the host, nothing is queued."""
+    L, Hq, Hkv, D = 4, 8, 2, 128
+    S = 64
+    dev = torch.device("cuda:0")
+    pool = torch.zeros((L, 64, 2 * 16 * Hkv * D), dtype=torch.bfloat16, device=dev)
+    big = torch.zeros((L, 4096, Hq, D), dtype=torch.bfloat16, device=dev)          # 32 MiB: an allocation of its own
+    out = torch.zeros((L, 4096, Hq, D), dtype=torch.bfloat16, device=dev)
+    kv = torch.zeros((L, 4096, Hkv, D), dtype=torch.bfloat16, device=dev)
+    ctx = cb.calvo_create(L, Hq, Hkv, D, cb.CALVO_BF16, 64, pool, staging_bytes=1 << 20)
+    try:
+        with dispatch.Dispatcher(ctx, cb.CALVO_POLICY_FIFO) as d:
+            table = np.arange(4, dtype=np.int32)
+            ok = dict(block_table=table, n_prefix_blocks=0, suffix_len=S, q=big, out=out, k_suffix=kv, v_suffix=kv,
+                      q_layer_stride=4096 * Hq * D * 2, out_layer_stride=4096 * Hq * D * 2, kv_layer_stride=4096 * Hkv * D * 2)
+            for bad in (dict(out_layer_stride=3 * 4096 * Hq * D * 2), dict(q_layer_stride=3 * 4096 * Hq * D * 2),
+                        dict(kv_layer_stride=3 * 4096 * Hkv * D * 2), dict(out_layer_stride=8), dict(q_layer_stride=24),
+                        dict(v_suffix=None), dict(out=None)):
+                with pytest.raises(cb.CalvoError) as ei:
+                    d.submit(**{**ok, **bad})
+                assert ei.value.code == cb.CALVO_EINVAL
+            assert d.stats()["jobs_submitted"] == 0
+            res = d.wait(d.submit(**ok))
+            assert res["status"] == 0
+    finally:
+        cb.calvo_destroy(ctx)
+    assert torch.isfinite(out[:, :S].float()).all()
+
+
 @pytest.mark.timing
 def test_the_link_stays_busy_while_other_requests_compute():
     """Link-bound service: four requests of 96 MiB each behind a 4 GB/s link, ample HBM.  The link
