@@ -466,8 +466,9 @@ int calvo_dispatch_table(calvo_dispatcher* d, int64_t id, int32_t* table, int32_
 int calvo_dispatch_release(calvo_dispatcher* d, int64_t id);
 int calvo_dispatch_stats_get(calvo_dispatcher* d, calvo_dispatch_stats* stats);
 /* Waits for every submitted job to finish - finished jobs that were not released are released by this
- * call, so jobs that wait for their slots go on - stops the threads, waits for the streams and frees
- * the dispatcher.  Must precede calvo_destroy. */
+ * call, so jobs that wait for their slots go on; jobs that still wait for slots when nothing else is
+ * left to finish (the slots are held outside the dispatcher) are failed with CALVO_ENOMEM - stops the
+ * threads, waits for the streams and frees the dispatcher.  Must precede calvo_destroy. */
 int calvo_dispatch_destroy(calvo_dispatcher* d);
 
 /* Measurement helper: duration in milliseconds of the most recent attention kernel queued by

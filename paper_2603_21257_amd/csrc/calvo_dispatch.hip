@@ -61,6 +61,7 @@ struct calvo_dispatcher {
   std::mutex mu;
   std::condition_variable cv;
   bool stop = false;
+  bool cancel_waiting = false;          // destroy: jobs that still wait for slots nobody will give back are failed
   std::vector<std::unique_ptr<Job>> jobs;
   std::deque<Chunk> pcie_q;             // blocks that have landed in the pinned ring, in link order
   std::deque<Job*> done_q;              // jobs whose compute has been queued, in that order
@@ -131,6 +132,13 @@ bool wait_granted(calvo_dispatcher* d, Job* j, std::unique_lock<std::mutex>& lk)
     const int rc = calvo_pool_retry(d->cfg.pool, j->ticket, j->table.data());
     if (rc == CALVO_OK) { j->granted = true; break; }
     if (rc != CALVO_ENOTREADY) { fail_job(d, j, rc); break; }
+    if (d->cancel_waiting) {
+      (void)calvo_pool_cancel(d->cfg.pool, j->ticket);
+      j->ticket = -1;
+      (void)fail(CALVO_ENOMEM, "the dispatcher was destroyed while the job waited for slots that are held outside it");
+      fail_job(d, j, CALVO_ENOMEM);
+      break;
+    }
     d->cv.wait_for(lk, std::chrono::milliseconds(2));       // woken by calvo_dispatch_release
   }
   if (j->res.reactive) j->res.alloc_wait_s += d->now() - t_begin;
@@ -176,8 +184,9 @@ void link_main(calvo_dispatcher* d) {
       continue;
     }
     const int L = c->cfg.n_layers;
-    for (int l = 0; l < L && !d->stop; l++) {
-      for (int64_t j0 = first; j0 < nblk && !d->stop; j0 += d->chunk_blocks) {
+    // (a job that has failed meanwhile - its admission was refused or withdrawn - is not streamed any further)
+    for (int l = 0; l < L && !d->stop && j->res.status == CALVO_OK; l++) {
+      for (int64_t j0 = first; j0 < nblk && !d->stop && j->res.status == CALVO_OK; j0 += d->chunk_blocks) {
         const int64_t nb = std::min<int64_t>(d->chunk_blocks, nblk - j0);
         const size_t bytes = (size_t)nb * c->blk_bytes;
         const int slot = (int)(k % (uint64_t)d->n_slots);
@@ -637,17 +646,30 @@ int calvo_dispatch_destroy(calvo_dispatcher* d) {
     // let the work that has been submitted finish, then stop the stages; finished jobs that nobody
     // released give their slots back now, so that jobs which wait for slots can go on
     std::unique_lock<std::mutex> lk(d->mu);
+    int quiet = 0;                          // consecutive rounds in which only slot waiters were left
     for (;;) {
-      bool all = true;
+      bool all = true, only_waiters = true, released_now = false;
       for (auto& j : d->jobs) {
-        if (!j->finished) { all = false; continue; }
+        if (!j->finished) {
+          all = false;
+          if (!(j->load_picked && !j->granted)) only_waiters = false;      // queued, loading or computing: will move by itself
+          continue;
+        }
         if (d->cfg.pool && j->granted && !j->released && j->n_tab > 0) {
           (void)calvo_pool_release(d->cfg.pool, j->table.data(), j->n_tab);
           j->released = true;
+          released_now = true;
           d->cv.notify_all();
         }
       }
       if (all) break;
+      // Everything that can finish has finished and given its slots back, and what is left still waits for
+      // slots: they are held outside this dispatcher, so those jobs are failed instead of waiting for ever.
+      quiet = (only_waiters && !released_now) ? quiet + 1 : 0;
+      if (quiet > 50) {
+        d->cancel_waiting = true;
+        d->cv.notify_all();
+      }
       d->cv.wait_for(lk, std::chrono::milliseconds(2));
     }
     d->stop = true;

@@ -275,3 +275,22 @@ def test_dry_run_random_trace_with_a_tight_pool_drains(policy):
         assert cb.calvo_pool_counts(pool) == {"free": 100, "used": 0, "refs": 0, "waiting": 0}
     finally:
         cb.calvo_pool_destroy(pool)
+
+
+def test_destroy_does_not_wait_for_slots_that_are_held_outside():
+    """The pool's slots are held by someone else: the job can never be admitted.  Closing the dispatcher fails it
+    instead of waiting for ever, and withdraws its admission."""
+    pool = cb.calvo_pool_create(8)
+    try:
+        held = cb.calvo_pool_reserve(pool, 6)
+        d = dispatch.Dispatcher(None, cb.CALVO_POLICY_FIFO, pool=pool)
+        i = d.submit(n_prefix_blocks=4, suffix_len=1, sim_load_s=0.0, sim_comp_s=0.0)      # 5 slots, 2 free
+        time.sleep(0.05)
+        assert d.poll(i) is None
+        t0 = time.perf_counter()
+        d.close()
+        assert time.perf_counter() - t0 < 5.0
+        assert cb.calvo_pool_counts(pool) == {"free": 2, "used": 6, "refs": 6, "waiting": 0}
+        cb.calvo_pool_release(pool, held)
+    finally:
+        cb.calvo_pool_destroy(pool)
