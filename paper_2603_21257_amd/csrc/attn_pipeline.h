@@ -520,17 +520,21 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
     ahead_sm = false;
   }
 
-  // ---- sub-tiles on or past the diagonal: synchronous load, plain path.  The ring slots are
+  // ---- sub-tiles on or past the diagonal: loaded synchronously, plain path.  The ring slots are
   // written again below (by requests and, for rows past the context, by plain LDS stores), so
-  // every request of the pipelined part has to have landed first.
+  // every request of the pipelined part has to have landed first.  There are at most
+  // tile tokens / 32 + 1 of them, fewer than ring slots: they are requested together and computed
+  // after one wait (a group of RING at a time, should there ever be more).
   wait_vm<0>();
   __syncthreads();
-  for (int j = n_pipe; j < n_sub; j++) {
-    request_tail(j);
+  for (int j0 = n_pipe; j0 < n_sub; j0 += RING) {
+    const int j1 = min(n_sub, j0 + RING);
+    for (int j = j0; j < j1; j++) request_tail(j);
     wait_vm<0>();
     __syncthreads();
-    const int k0 = (jb + j) * kSK;
-    if (wave_active && k0 <= pq_max) {
+    for (int j = j0; j < j1; j++) {
+      const int k0 = (jb + j) * kSK;
+      if (!(wave_active && k0 <= pq_max)) continue;
       STile s;
       qk(j & RM, s);
       if (k0 + 31 > pq_min) {
@@ -549,7 +553,7 @@ __device__ __forceinline__ void attn_pipeline(const AttnParams& p, unsigned char
       if (__builtin_amdgcn_ballot_w64(changed) != 0) rescale(alpha);
       pv(j & RM, pb);
     }
-    __syncthreads();
+    if (j1 < n_sub) __syncthreads();      // the next group overwrites these slots
   }
 
   // ---- one piece of a split tile: leave the unnormalised O, the reference (exponent units) and
