@@ -281,6 +281,18 @@ def main():
         # transfers, and a layer's signal then fires with its group's).
         if not args.no_alap and args.tail_chunks > 0 and not head_chunks and w.ingest_bytes() / L >= (128 << 20):
             set_alap(t_ing, t_att)
+            # the chain must not cost TTFT: two untimed steps each way decide (the stage times it was derived from
+            # were measured in isolation)
+            chain, plain = plan["after"], list(range(L))
+            if chain != plain:
+                step()
+                t_chain = min(timed(step) for _ in range(2))
+                plan["after"] = plain
+                t_plain = min(timed(step) for _ in range(2))
+                keep = t_chain <= 1.002 * t_plain
+                plan["after"] = chain if keep else plain
+                log(f"[bench] attention launches queued back to back: step {t_chain:.2f} ms against {t_plain:.2f} ms with one launch "
+                    f"per landed layer: {'kept' if keep else 'dropped'}")
         # the interpreter's cyclic collector would otherwise run a full pass (tens of milliseconds with torch
         # loaded) in the middle of some step's enqueue loop
         import gc
